@@ -1,0 +1,133 @@
+/*
+ * mecefo.h -- C ABI of the MI355X (gfx950) degraded transformer-block backward of
+ * MeCeFO (arxiv 2510.16415).
+ *
+ * What the calls compute (paper passages they follow):
+ *   - Alg. 3, neighbor branch: recompute the FFN activations from the one stored
+ *     tensor, form the three FFN weight gradients with Eq. (2), skip the MHA
+ *     connection and hand the activation gradient to the previous layer.
+ *   - Sec. 3.2 (skip-connection): the MHA branch is cut in the backward pass only;
+ *     no MHA parameter gets a gradient on this rank.
+ *   - Sec. 3.3 (selective recomputation): only the input of the FFN module is kept.
+ *   - Sec. 3.4 Eq. (2): G_W = G_y x^T ~= G_y (x^T V1) V1^T, V1 in R^{n x r}.
+ *   - Sec. 2: LLaMA block, FFN = W_down( silu(W_gate u) * (W_up u) ), RMSNorm, residual.
+ *
+ * Notation (row-major, token index along rows, weights in [out x in] layout):
+ *   b tokens, d = d_model, f = d_ff, r = rank.
+ *   H  [b x d]  stored FFN-module input (residual stream before the FFN norm)
+ *   U  [b x d]  = RMSNorm(H) * gamma          Wg, Wu [f x d]   Wd [d x f]
+ *   G = U Wg^T, Z = U Wu^T [b x f];  S = silu(G);  A = S*Z;  Y = A Wd^T;  Out = H + Y.
+ *
+ * Memory and ownership: EVERY data pointer is a DEVICE pointer owned by the caller
+ * (descriptors and size outputs are host memory).  The library allocates and frees
+ * nothing; scratch comes from the caller's workspace, sized by
+ * mecefo_workspace_bytes().  Calls only enqueue work on the given HIP stream
+ * (a hipStream_t passed as void*, NULL = default stream) and return without
+ * synchronising.  Workspace contents are undefined after a call; two calls that
+ * share a workspace must be ordered on the same stream.
+ *
+ * Layout rules: every matrix is row-major with an explicit row stride in elements.
+ * dtype MECEFO_BF16: storage bf16, fp32 accumulation in MFMA; all data pointers must
+ * be 16-byte aligned and all row strides multiples of 8 elements (so an odd d_ff such
+ * as 5461 needs ld >= 5464); columns between the logical width and the stride are
+ * never read as data.  dtype MECEFO_F32: no alignment rule beyond 4 bytes.
+ * Every tensor must be smaller than 2 GiB.  With tokens == 0 the [b x *] pointers may be NULL.
+ *
+ * Errors: argument checks happen on the host before anything is enqueued; on a
+ * non-OK status nothing was launched by that call (MECEFO_ERR_LAUNCH excepted) and
+ * mecefo_last_error() returns a thread-local description.  No C++ exception
+ * crosses this boundary.
+ */
+#ifndef MECEFO_H_
+#define MECEFO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MECEFO_OK = 0,
+  MECEFO_ERR_INVALID_ARG = 1,          /* NULL required pointer, bad size/stride/alignment/rank */
+  MECEFO_ERR_UNSUPPORTED = 2,          /* dtype combination or size not built */
+  MECEFO_ERR_WORKSPACE_TOO_SMALL = 3,
+  MECEFO_ERR_LAUNCH = 4                /* HIP reported an error while enqueuing */
+} mecefo_status_t;
+
+typedef enum { MECEFO_F32 = 0, MECEFO_BF16 = 1 } mecefo_dtype_t;
+
+/* Which side of y = W x Eq. (2) projects.
+ * MECEFO_SIDE_INPUT  (the paper's form): P = V1 in R^{n_in x r};  dW = (Gy^T (X P)) P^T.
+ * MECEFO_SIDE_OUTPUT (mirror form):      P in R^{m_out x r};      dW = P ((X^T (Gy P)))^T. */
+typedef enum { MECEFO_SIDE_INPUT = 0, MECEFO_SIDE_OUTPUT = 1 } mecefo_side_t;
+
+typedef struct {
+  int64_t tokens;               /* b */
+  int32_t d_model, d_ff;        /* d, f */
+  int64_t ld_act_d, ld_act_f;   /* row strides of caller [b x d] and [b x f] tensors (>= d, >= f) */
+  int64_t ld_w_fd, ld_w_df;     /* row strides of Wg/Wu/dWg/dWu [f x d] and Wd/dWd [d x f] */
+  mecefo_dtype_t dtype;         /* activations, weights, projections */
+  mecefo_dtype_t grad_dtype;    /* dWg/dWu/dWd/dgamma buffers: MECEFO_F32, or equal to dtype */
+  float rms_eps;                /* RMSNorm epsilon; used only when gamma != NULL */
+} mecefo_ffn_desc_t;
+
+/* Projection matrix, row-major [dim x r] with row stride ld (>= r).  dim is the
+ * projected dimension: SIDE_INPUT: d for gate/up, f for down; SIDE_OUTPUT: f for
+ * gate/up, d for down.  1 <= r <= dim.  P is opaque data: it need not be orthonormal
+ * nor related to the current weights (Alg. 3 reuses it for tau steps). */
+typedef struct { const void* P; int32_t r; int64_t ld; } mecefo_proj_t;
+
+/* Bytes of workspace that any of the calls below needs for this descriptor and these
+ * ranks (pass the largest ranks you will use; 0 if only the non-low-rank calls are used). */
+mecefo_status_t mecefo_workspace_bytes(const mecefo_ffn_desc_t* desc, int r_gate, int r_up,
+                                       int r_down, size_t* out_bytes);
+
+/* Sec. 3.3 Rcomp.  In: U [b x d] (ld_act_d), Wg, Wu [f x d], Wd [d x f] or NULL.
+ * Out: G, Z, A [b x f] (ld_act_f); Y [b x d] (ld_act_d) = A Wd^T, or NULL to skip the
+ * down projection (the backward never needs it).  Any of G, Z may be NULL (not stored). */
+mecefo_status_t mecefo_ffn_fwd_recompute(const mecefo_ffn_desc_t* desc, const void* U,
+    const void* Wg, const void* Wu, const void* Wd,
+    void* G, void* Z, void* A, void* Y, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Exact FFN backward (the comparator Eq. (2) approximates).  In: U, dY [b x d];
+ * weights; G, Z [b x f] saved activations, or both NULL to recompute them from U.
+ * Out: dU [b x d] (may be NULL), dWg, dWu [f x d], dWd [d x f] in grad_dtype.
+ * accumulate = 0 overwrites the dW buffers, 1 adds to them. */
+mecefo_status_t mecefo_ffn_bwd_exact(const mecefo_ffn_desc_t* desc, const void* U, const void* dY,
+    const void* Wg, const void* Wu, const void* Wd, const void* G, const void* Z,
+    void* dU, void* dWg, void* dWu, void* dWd, int accumulate,
+    void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Alg. 3 neighbor branch, FFN part: recompute from U, exact dU, Eq. (2) weight gradients. */
+mecefo_status_t mecefo_ffn_bwd_lowrank(const mecefo_ffn_desc_t* desc, const void* U, const void* dY,
+    const void* Wg, const void* Wu, const void* Wd,
+    mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+    void* dU, void* dWg, void* dWu, void* dWd, int accumulate,
+    void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Whole neighbor-mode backward of one block (Alg. 3: recompute, Eq. (2), skip MHA).
+ * In: H [b x d] stored FFN-module input; dOut [b x d] gradient of the block output;
+ * gamma [d] FFN-norm gain (dtype), or NULL meaning the stored tensor feeds the FFN
+ * directly (U = H).  Out: dX [b x d] = dOut + normbwd(dU): the gradient handed to the
+ * previous layer (the MHA branch contributes nothing); dX may alias dOut.  dgamma [d]
+ * in grad_dtype or NULL.  dWg, dWu, dWd as above.  No MHA weight or gradient buffer is
+ * an argument: this rank produces none (Sec. 3.2). */
+mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void* H,
+    const void* dOut, const void* gamma,
+    const void* Wg, const void* Wu, const void* Wd,
+    mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+    void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
+    void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Description of the last non-OK status returned on this thread ("" if none). */
+const char* mecefo_last_error(void);
+
+/* Library version string (static storage). */
+const char* mecefo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MECEFO_H_ */

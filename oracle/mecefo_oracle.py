@@ -184,28 +184,28 @@ def _rope(x, cos, sin, inverse=False):
     return np.concatenate([x1 * cos - x2 * s, x1 * s + x2 * cos], axis=-1)
 
 
-def mha_fwd(X, g_attn, Wq, Wk, Wv, Wo, heads, batch, seq, eps=1e-6):
+def mha_fwd(X, g_attn, Wq, Wk, Wv, Wo, heads, batch, seq, eps=1e-6, dtype=np.float64):
     """Pre-norm causal multi-head attention with RoPE; returns branch output and a cache."""
-    X = _f(X, np.float64)
+    X = _f(X, dtype)
     d = X.shape[1]
     dh = d // heads
-    Xn, N, rstd = rmsnorm_fwd(X, g_attn, eps)
+    Xn, N, rstd = rmsnorm_fwd(X, g_attn, eps, dtype)
 
     def split(t):
         return t.reshape(batch, seq, heads, dh).transpose(0, 2, 1, 3)
 
-    cos, sin = _rope_tables(seq, dh)
-    Q = _rope(split(Xn @ _f(Wq, np.float64).T), cos, sin)
-    K = _rope(split(Xn @ _f(Wk, np.float64).T), cos, sin)
-    V = split(Xn @ _f(Wv, np.float64).T)
-    sc = (Q @ K.transpose(0, 1, 3, 2)) / np.sqrt(dh)
+    cos, sin = (_f(t, dtype) for t in _rope_tables(seq, dh))
+    Q = _rope(split(Xn @ _f(Wq, dtype).T), cos, sin)
+    K = _rope(split(Xn @ _f(Wk, dtype).T), cos, sin)
+    V = split(Xn @ _f(Wv, dtype).T)
+    sc = (Q @ K.transpose(0, 1, 3, 2)) / dtype(np.sqrt(dh))
     mask = np.triu(np.ones((seq, seq), dtype=bool), 1)
     sc = np.where(mask, -np.inf, sc)
     sc = sc - sc.max(axis=-1, keepdims=True)
     Pm = np.exp(sc)
     Pm /= Pm.sum(axis=-1, keepdims=True)
     O = (Pm @ V).transpose(0, 2, 1, 3).reshape(batch * seq, d)
-    M = O @ _f(Wo, np.float64).T
+    M = O @ _f(Wo, dtype).T
     cache = dict(Xn=Xn, N=N, rstd=rstd, Q=Q, K=K, V=V, Pm=Pm, O=O, cos=cos, sin=sin,
                  heads=heads, batch=batch, seq=seq)
     return M, cache
@@ -237,13 +237,13 @@ def mha_bwd(dM, cache, g_attn, Wq, Wk, Wv, Wo):
     return dX_branch, dict(dWq=dWq, dWk=dWk, dWv=dWv, dWo=dWo, dg_attn=dg_attn)
 
 
-def block_fwd_full(X, p, heads, batch, seq, eps=1e-6):
+def block_fwd_full(X, p, heads, batch, seq, eps=1e-6, dtype=np.float64):
     """Standard forward of one block: H = X + MHA(norm(X)); Out = H + FFN(norm(H))."""
-    X = _f(X, np.float64)
-    M, cache = mha_fwd(X, p["g_attn"], p["Wq"], p["Wk"], p["Wv"], p["Wo"], heads, batch, seq, eps)
+    X = _f(X, dtype)
+    M, cache = mha_fwd(X, p["g_attn"], p["Wq"], p["Wk"], p["Wv"], p["Wo"], heads, batch, seq, eps, dtype)
     H = X + M
-    U, _, _ = rmsnorm_fwd(H, p["g_ffn"], eps)
-    _, _, _, Y = ffn_fwd_recompute(U, p["Wg"], p["Wu"], p["Wd"])
+    U, _, _ = rmsnorm_fwd(H, p["g_ffn"], eps, dtype)
+    _, _, _, Y = ffn_fwd_recompute(U, p["Wg"], p["Wu"], p["Wd"], dtype)
     return H + Y, H, cache
 
 
@@ -260,14 +260,19 @@ def block_bwd_full(X, dOut, p, heads, batch, seq, eps=1e-6):
 
 
 # ------------------------------------------------ token-stack harness (inputs only)
-def stack_forward(ids, params, heads, eps=1e-6):
-    """Embedding -> L blocks; returns the stored FFN inputs H_l and the last block's output."""
+def stack_forward(ids, params, heads, eps=1e-6, dtype=np.float64, keep_last=None):
+    """Embedding -> L blocks; returns the stored FFN inputs H_l and the last block's output.
+
+    This only manufactures realistic inputs (H_l, and through the loss dOut_L) for the
+    path under test, so callers may run it in float32 for speed and keep only the
+    last `keep_last` H_l; the degraded backward itself is always checked in fp64."""
     batch, seq = ids.shape
-    X = _f(params["emb"], np.float64)[ids.reshape(-1)]
+    X = _f(params["emb"][ids.reshape(-1)], dtype)
     Hs = []
-    for p in params["blocks"]:
-        X, H, _ = block_fwd_full(X, p, heads, batch, seq, eps)
-        Hs.append(H)
+    L = len(params["blocks"])
+    for li, p in enumerate(params["blocks"]):
+        X, H, _ = block_fwd_full(X, p, heads, batch, seq, eps, dtype)
+        Hs.append(H if keep_last is None or li >= L - keep_last else None)
     return Hs, X
 
 

@@ -1,0 +1,458 @@
+// C ABI of the degraded block backward: argument validation, workspace carving and the
+// order in which the kernels are enqueued.  Every arithmetic step runs in the kernels.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/mecefo.h"
+#include "gemm_bf16_launch.hip.h"
+#include "mecefo_internal.h"
+
+using namespace mecefo;
+
+namespace mecefo {
+hipError_t launch_gemm(GemmLaunch& g, hipStream_t s) {
+  if (!g.bf16) return launch_gemm_f32(g, s);
+  if (g.a_kcontig && g.b_kcontig) return launch_gemm_bf16_nt(g, s);
+  if (g.a_kcontig && !g.b_kcontig) return launch_gemm_bf16_nn(g, s);
+  if (!g.a_kcontig && !g.b_kcontig) return launch_gemm_bf16_tn(g, s);
+  return hipErrorInvalidValue;
+}
+}  // namespace mecefo
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+mecefo_status_t fail(mecefo_status_t st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+constexpr int64_t kMaxBytes = (int64_t)1 << 31;
+
+inline int64_t up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+struct Ctx {
+  const mecefo_ffn_desc_t* d;
+  bool bf16;
+  int esz;          // bytes per activation element
+  int64_t b;
+  int dm, ff;
+  int64_t ldf;      // row stride of internal [b x f] buffers
+  bool grad_f32;
+};
+
+mecefo_status_t check_desc(const mecefo_ffn_desc_t* d, Ctx* c) {
+  if (!d) return fail(MECEFO_ERR_INVALID_ARG, "descriptor is NULL");
+  if (d->dtype != MECEFO_F32 && d->dtype != MECEFO_BF16)
+    return fail(MECEFO_ERR_INVALID_ARG, "dtype must be MECEFO_F32 or MECEFO_BF16");
+  if (d->grad_dtype != MECEFO_F32 && d->grad_dtype != d->dtype)
+    return fail(MECEFO_ERR_UNSUPPORTED, "grad_dtype must be MECEFO_F32 or equal to dtype");
+  if (d->tokens < 0 || d->d_model < 1 || d->d_ff < 1)
+    return fail(MECEFO_ERR_INVALID_ARG, "tokens >= 0, d_model >= 1, d_ff >= 1 required");
+  if (d->ld_act_d < d->d_model || d->ld_act_f < d->d_ff || d->ld_w_fd < d->d_model || d->ld_w_df < d->d_ff)
+    return fail(MECEFO_ERR_INVALID_ARG, "a row stride is smaller than the logical width");
+  c->d = d;
+  c->bf16 = d->dtype == MECEFO_BF16;
+  c->esz = c->bf16 ? 2 : 4;
+  c->b = d->tokens;
+  c->dm = d->d_model;
+  c->ff = d->d_ff;
+  c->ldf = up(d->d_ff, 8);
+  c->grad_f32 = d->grad_dtype == MECEFO_F32;
+  if (c->bf16) {
+    if (d->d_model % 8)
+      return fail(MECEFO_ERR_UNSUPPORTED, "bf16 path needs d_model to be a multiple of 8 (got %d)", d->d_model);
+    if (d->ld_act_d % 8 || d->ld_act_f % 8 || d->ld_w_fd % 8 || d->ld_w_df % 8)
+      return fail(MECEFO_ERR_INVALID_ARG,
+                  "bf16 path needs every row stride to be a multiple of 8 elements (pad d_ff=%d to %lld)",
+                  d->d_ff, (long long)up(d->d_ff, 8));
+  }
+  const int64_t big = d->tokens * (d->ld_act_f > d->ld_act_d ? d->ld_act_f : d->ld_act_d);
+  const int64_t wbig = (int64_t)d->d_ff * d->ld_w_fd > (int64_t)d->d_model * d->ld_w_df
+                           ? (int64_t)d->d_ff * d->ld_w_fd : (int64_t)d->d_model * d->ld_w_df;
+  if (big * c->esz >= kMaxBytes || wbig * 4 >= kMaxBytes)
+    return fail(MECEFO_ERR_UNSUPPORTED, "a tensor reaches 2 GiB; split the token batch");
+  return MECEFO_OK;
+}
+
+mecefo_status_t check_ptr(const Ctx& c, const void* p, const char* name, bool required = true) {
+  if (!p) return required ? fail(MECEFO_ERR_INVALID_ARG, "%s is NULL", name) : MECEFO_OK;
+  if (((uintptr_t)p) % (c.bf16 ? 16 : 4)) return fail(MECEFO_ERR_INVALID_ARG, "%s is not %d-byte aligned", name, c.bf16 ? 16 : 4);
+  return MECEFO_OK;
+}
+
+mecefo_status_t check_proj(const Ctx& c, const mecefo_proj_t& P, int dim, const char* name) {
+  if (!P.P) return fail(MECEFO_ERR_INVALID_ARG, "projection %s is NULL", name);
+  if (P.r < 1 || P.r > dim) return fail(MECEFO_ERR_INVALID_ARG, "projection %s: rank %d outside [1, %d]", name, P.r, dim);
+  if (P.ld < P.r) return fail(MECEFO_ERR_INVALID_ARG, "projection %s: ld %lld < r %d", name, (long long)P.ld, P.r);
+  if (c.bf16 && (P.ld % 8 || ((uintptr_t)P.P) % 16))
+    return fail(MECEFO_ERR_INVALID_ARG, "projection %s: bf16 path needs ld %% 8 == 0 and a 16-byte aligned pointer", name);
+  return MECEFO_OK;
+}
+
+#define TRY(x) do { mecefo_status_t st__ = (x); if (st__ != MECEFO_OK) return st__; } while (0)
+#define HIP_TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return fail(MECEFO_ERR_LAUNCH, "%s: %s", #x, hipGetErrorString(e__)); } while (0)
+
+// ---- workspace ------------------------------------------------------------------------
+struct Workspace {
+  // offsets in bytes from the (256-byte aligned) workspace base
+  size_t U, rstd, DG, DZ, AA, dU, T[3], C[3], partial, dgp, total;
+  int splits;
+  int64_t c_elems[3];
+};
+
+// Split count for the token contraction of Eq. (2): the outputs ([f x r], [d x r]) are small, so
+// the long token dimension is cut to get enough workgroups for 256 CUs.
+int choose_splits(const Ctx& c, const int64_t c_rows[3], const int r[3]) {
+  int tiles_l = 0, tiles_s = 0, tiles_f = 0;
+  for (int i = 0; i < 3; ++i) {
+    if (r[i] <= 0) continue;
+    tiles_l += cdiv((int)c_rows[i], 256) * cdiv(r[i], 256);
+    tiles_s += cdiv((int)c_rows[i], 128) * cdiv(r[i], 128);
+    tiles_f += cdiv((int)c_rows[i], 64) * cdiv(r[i], 64);
+  }
+  int tiles, ktiles, target;
+  if (!c.bf16) { tiles = tiles_f; ktiles = cdiv((int)c.b, 16); target = 512; }
+  else if (tiles_l >= 160) { tiles = tiles_l; ktiles = cdiv((int)c.b, 64); target = 256; }
+  else { tiles = tiles_s; ktiles = cdiv((int)c.b, 64); target = 512; }
+  if (tiles == 0) return 1;
+  int s = cdiv(target, tiles);
+  const int smax = ktiles / 4 > 1 ? ktiles / 4 : 1;
+  if (s > smax) s = smax;
+  if (s > 16) s = 16;
+  return s < 1 ? 1 : s;
+}
+
+Workspace layout(const Ctx& c, const int r[3], mecefo_side_t side, int force_splits) {
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += (size_t)up((int64_t)bytes, 256); return o; };
+  const size_t act_d = (size_t)c.b * c.dm * c.esz, act_f = (size_t)c.b * c.ldf * c.esz;
+  w.U = take(act_d);
+  w.rstd = take((size_t)c.b * 4);
+  w.DG = take(act_f);
+  w.DZ = take(act_f);
+  w.AA = take(act_f);
+  w.dU = take(act_d);
+  // C_i rows: SIDE_INPUT: gate/up -> f, down -> d (output dim); SIDE_OUTPUT: gate/up -> d, down -> f.
+  int64_t c_rows[3];
+  c_rows[0] = c_rows[1] = side == MECEFO_SIDE_INPUT ? c.ff : c.dm;
+  c_rows[2] = side == MECEFO_SIDE_INPUT ? c.dm : c.ff;
+  int64_t sum_c = 0;
+  for (int i = 0; i < 3; ++i) {
+    const int64_t rr = up(r[i] > 0 ? r[i] : 0, 8);
+    w.T[i] = take((size_t)c.b * rr * c.esz);
+    w.c_elems[i] = c_rows[i] * rr;
+    w.C[i] = take((size_t)w.c_elems[i] * c.esz);
+    sum_c += c_rows[i] * rr;
+  }
+  w.splits = force_splits > 0 ? force_splits : choose_splits(c, c_rows, r);
+  w.partial = take(w.splits > 1 ? (size_t)w.splits * sum_c * 4 : 0);
+  w.dgp = take((size_t)rmsnorm_bwd_blocks(c.b) * c.dm * 4);
+  w.total = off + 256;   // slack for aligning the caller's base pointer
+  return w;
+}
+
+struct Bufs { char* base; Workspace w; };
+
+mecefo_status_t carve(const Ctx& c, const int r[3], mecefo_side_t side, void* ws, size_t ws_bytes, Bufs* out) {
+  Workspace w = layout(c, r, side, 0);
+  while (w.total > ws_bytes && w.splits > 1) w = layout(c, r, side, w.splits - 1);
+  if (w.total > ws_bytes)
+    return fail(MECEFO_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, w.total);
+  if (!ws) return fail(MECEFO_ERR_INVALID_ARG, "workspace is NULL");
+  out->base = (char*)up((int64_t)(uintptr_t)ws, 256);
+  out->w = w;
+  return MECEFO_OK;
+}
+
+GemmLaunch new_launch(const Ctx& c, bool akc, bool bkc, int epi) {
+  GemmLaunch g;
+  memset(&g, 0, sizeof(g));
+  g.a_kcontig = akc;
+  g.b_kcontig = bkc;
+  g.epi = epi;
+  g.bf16 = c.bf16;
+  g.out_f32 = c.grad_f32;
+  g.splits = 1;
+  return g;
+}
+
+GemmProblem prob(const void* A0, const void* A1, int64_t lda, const void* B0, const void* B1, int64_t ldb,
+                 void* C0, void* C1, void* C2, int64_t ldc, int M, int N, int K, int nseg, int pad_cols = 0) {
+  GemmProblem p;
+  memset(&p, 0, sizeof(p));
+  p.A[0] = A0; p.A[1] = A1 ? A1 : A0;
+  p.B[0] = B0; p.B[1] = B1 ? B1 : B0;
+  p.C[0] = C0; p.C[1] = C1; p.C[2] = C2;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.M = M; p.N = N; p.K = K; p.nseg = nseg; p.pad_cols = pad_cols;
+  return p;
+}
+
+// dA = dY Wd  ->  recompute G, Z from U and apply the SwiGLU backward in the epilogue
+// (DG = dG, DZ = dZ, AA = A)  ->  dU = dG Wg + dZ Wu.   Sec. 3.3 (Rcomp) + exact Dgrad.
+mecefo_status_t recompute_and_dgrad(const Ctx& c, const Bufs& bf, const void* U, int64_t ldu, const void* dY,
+                                    int64_t lddy, const void* Wg, const void* Wu, const void* Wd,
+                                    const void* Gsaved, const void* Zsaved, void* dU, int64_t lddu,
+                                    hipStream_t s) {
+  const mecefo_ffn_desc_t& d = *c.d;
+  char* base = bf.base;
+  void* DG = base + bf.w.DG; void* DZ = base + bf.w.DZ; void* AA = base + bf.w.AA;
+  const int b = (int)c.b;
+  if (b == 0) return MECEFO_OK;
+  {  // dA = dY Wd   [b x f], K = d
+    GemmLaunch g = new_launch(c, true, false, EPI_STORE);
+    g.nprob = 1;
+    g.p[0] = prob(dY, nullptr, lddy, Wd, nullptr, d.ld_w_df, DG, nullptr, nullptr, c.ldf, b, c.ff, c.dm, 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  if (Gsaved) {
+    HIP_TRY(launch_swiglu_bwd(c.bf16, Gsaved, Zsaved, d.ld_act_f, DG, DZ, AA, c.ldf, c.b, c.ff, (int)c.ldf, s));
+  } else {  // G = U Wg^T, Z = U Wu^T with the SwiGLU backward fused into the epilogue
+    GemmLaunch g = new_launch(c, true, true, EPI_SWIGLU_BWD);
+    g.nprob = 1;
+    g.p[0] = prob(U, nullptr, ldu, Wg, Wu, d.ld_w_fd, DG, DZ, AA, c.ldf, b, c.ff, c.dm, 1, (int)c.ldf);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  if (dU) {  // dU = dG Wg + dZ Wu   [b x d], two K segments of length f
+    GemmLaunch g = new_launch(c, true, false, EPI_STORE);
+    g.nprob = 1;
+    g.p[0] = prob(DG, DZ, c.ldf, Wg, Wu, d.ld_w_fd, dU, nullptr, nullptr, lddu, b, c.dm, c.ff, 2);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  return MECEFO_OK;
+}
+
+// Eq. (2) for the three FFN matrices, each as project -> contract over tokens -> expand.
+//   SIDE_INPUT : T = X P [b x r];  C = Gy^T T [m x r];  dW [m x n] = C P^T.
+//   SIDE_OUTPUT: T = Gy P [b x r]; C = X^T T [n x r];   dW [m x n] = P C^T.
+// gate: (Gy, X) = (dG, U); up: (dZ, U); down: (dY, A).
+mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64_t ldu, const void* dY,
+                              int64_t lddy, const mecefo_proj_t P[3], mecefo_side_t side, void* dW[3],
+                              int accumulate, hipStream_t s) {
+  const mecefo_ffn_desc_t& d = *c.d;
+  char* base = bf.base;
+  const int b = (int)c.b;
+  const void* Gy[3] = {base + bf.w.DG, base + bf.w.DZ, dY};
+  const int64_t ldgy[3] = {c.ldf, c.ldf, lddy};
+  const void* X[3] = {U, U, base + bf.w.AA};
+  const int64_t ldx[3] = {ldu, ldu, c.ldf};
+  const int m_out[3] = {c.ff, c.ff, c.dm};   // rows of dW
+  const int n_in[3] = {c.dm, c.dm, c.ff};    // cols of dW
+  const int64_t lddw[3] = {d.ld_w_fd, d.ld_w_fd, d.ld_w_df};
+  const bool in = side == MECEFO_SIDE_INPUT;
+  int64_t ldt[3];
+  void* T[3];
+  void* C[3];
+  for (int i = 0; i < 3; ++i) { ldt[i] = up(P[i].r, 8); T[i] = base + bf.w.T[i]; C[i] = base + bf.w.C[i]; }
+
+  if (b > 0) {  // project: T = (X or Gy) P, contraction over the projected dimension
+    GemmLaunch g = new_launch(c, true, false, EPI_STORE);
+    g.nprob = 3;
+    for (int i = 0; i < 3; ++i)
+      g.p[i] = prob(in ? X[i] : Gy[i], nullptr, in ? ldx[i] : ldgy[i], P[i].P, nullptr, P[i].ld, T[i], nullptr,
+                    nullptr, ldt[i], b, P[i].r, in ? n_in[i] : m_out[i], 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  {  // contract over tokens: C = (Gy or X)^T T   [rows x r], K = b
+    const int splits = b > 0 ? bf.w.splits : 1;
+    GemmLaunch g = new_launch(c, false, false, splits > 1 ? EPI_SPLIT_F32 : EPI_STORE);
+    g.nprob = 3;
+    g.splits = splits;
+    g.partial = (float*)(base + bf.w.partial);
+    int64_t poff = 0;
+    for (int i = 0; i < 3; ++i) {
+      const int rows = in ? m_out[i] : n_in[i];
+      g.p[i] = prob(in ? Gy[i] : X[i], nullptr, in ? ldgy[i] : ldx[i], T[i], nullptr, ldt[i], C[i], nullptr,
+                    nullptr, ldt[i], rows, P[i].r, b, 1);
+      g.partial_off[i] = poff;
+      poff += (int64_t)splits * rows * ldt[i];
+    }
+    HIP_TRY(launch_gemm(g, s));
+    if (splits > 1) {
+      // partial of problem i is [split][rows x ldt]; the reduction keeps that row stride
+      for (int i = 0; i < 3; ++i) {
+        const int rows = in ? m_out[i] : n_in[i];
+        HIP_TRY(launch_splitk_reduce(c.bf16, g.partial + g.partial_off[i], splits, (int64_t)rows * ldt[i], C[i], s));
+      }
+    }
+  }
+  {  // expand: dW = C P^T (SIDE_INPUT) or P C^T (SIDE_OUTPUT), K = r, into the gradient buffers
+    GemmLaunch g = new_launch(c, true, true, EPI_GRAD);
+    g.nprob = 3;
+    g.accumulate = accumulate;
+    for (int i = 0; i < 3; ++i)
+      g.p[i] = in ? prob(C[i], nullptr, ldt[i], P[i].P, nullptr, P[i].ld, dW[i], nullptr, nullptr, lddw[i],
+                         m_out[i], n_in[i], P[i].r, 1)
+                  : prob(P[i].P, nullptr, P[i].ld, C[i], nullptr, ldt[i], dW[i], nullptr, nullptr, lddw[i],
+                         m_out[i], n_in[i], P[i].r, 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  return MECEFO_OK;
+}
+
+mecefo_status_t check_lowrank_args(const Ctx& c, const mecefo_proj_t P[3], mecefo_side_t side) {
+  if (side != MECEFO_SIDE_INPUT && side != MECEFO_SIDE_OUTPUT) return fail(MECEFO_ERR_INVALID_ARG, "side must be MECEFO_SIDE_INPUT or MECEFO_SIDE_OUTPUT");
+  const bool in = side == MECEFO_SIDE_INPUT;
+  TRY(check_proj(c, P[0], in ? c.dm : c.ff, "Pg"));
+  TRY(check_proj(c, P[1], in ? c.dm : c.ff, "Pu"));
+  TRY(check_proj(c, P[2], in ? c.ff : c.dm, "Pd"));
+  return MECEFO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mecefo_last_error(void) { return g_err; }
+const char* mecefo_version(void) { return "mecefo-gfx950 0.1"; }
+
+mecefo_status_t mecefo_workspace_bytes(const mecefo_ffn_desc_t* desc, int r_gate, int r_up, int r_down,
+                                       size_t* out_bytes) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  if (!out_bytes) return fail(MECEFO_ERR_INVALID_ARG, "out_bytes is NULL");
+  if (r_gate < 0 || r_up < 0 || r_down < 0) return fail(MECEFO_ERR_INVALID_ARG, "ranks must be >= 0");
+  const int r[3] = {r_gate, r_up, r_down};
+  const size_t a = layout(c, r, MECEFO_SIDE_INPUT, 0).total;
+  const size_t b2 = layout(c, r, MECEFO_SIDE_OUTPUT, 0).total;
+  *out_bytes = a > b2 ? a : b2;
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_ffn_fwd_recompute(const mecefo_ffn_desc_t* desc, const void* U, const void* Wg,
+                                         const void* Wu, const void* Wd, void* G, void* Z, void* A, void* Y,
+                                         void* ws, size_t ws_bytes, void* hip_stream) {
+  (void)ws; (void)ws_bytes;
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_ptr(c, U, "U")); TRY(check_ptr(c, Wg, "Wg")); TRY(check_ptr(c, Wu, "Wu"));
+  TRY(check_ptr(c, G, "G", false)); TRY(check_ptr(c, Z, "Z", false)); TRY(check_ptr(c, A, "A"));
+  TRY(check_ptr(c, Y, "Y", false));
+  if (Y) TRY(check_ptr(c, Wd, "Wd (needed for Y)"));
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int b = (int)c.b;
+  if (b == 0) return MECEFO_OK;
+  const int pad = (int)(up(c.ff, 8) <= desc->ld_act_f ? up(c.ff, 8) : c.ff);
+  {
+    GemmLaunch g = new_launch(c, true, true, EPI_SWIGLU_FWD);
+    g.nprob = 1;
+    g.p[0] = prob(U, nullptr, desc->ld_act_d, Wg, Wu, desc->ld_w_fd, G, Z, A, desc->ld_act_f, b, c.ff, c.dm, 1, pad);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  if (Y) {  // Y = A Wd^T   [b x d], K = f
+    GemmLaunch g = new_launch(c, true, true, EPI_STORE);
+    g.nprob = 1;
+    g.p[0] = prob(A, nullptr, desc->ld_act_f, Wd, nullptr, desc->ld_w_df, Y, nullptr, nullptr, desc->ld_act_d, b, c.dm, c.ff, 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_ffn_bwd_exact(const mecefo_ffn_desc_t* desc, const void* U, const void* dY,
+                                     const void* Wg, const void* Wu, const void* Wd, const void* G,
+                                     const void* Z, void* dU, void* dWg, void* dWu, void* dWd, int accumulate,
+                                     void* ws, size_t ws_bytes, void* hip_stream) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_ptr(c, U, "U", c.b > 0)); TRY(check_ptr(c, dY, "dY", c.b > 0));
+  TRY(check_ptr(c, Wg, "Wg")); TRY(check_ptr(c, Wu, "Wu")); TRY(check_ptr(c, Wd, "Wd"));
+  if ((G == nullptr) != (Z == nullptr)) return fail(MECEFO_ERR_INVALID_ARG, "G and Z must both be given or both be NULL");
+  TRY(check_ptr(c, G, "G", false)); TRY(check_ptr(c, Z, "Z", false)); TRY(check_ptr(c, dU, "dU", false));
+  if (!dWg || !dWu || !dWd) return fail(MECEFO_ERR_INVALID_ARG, "dWg, dWu, dWd are required");
+  if (c.bf16 && (((uintptr_t)dWg | (uintptr_t)dWu | (uintptr_t)dWd) % 16)) return fail(MECEFO_ERR_INVALID_ARG, "gradient buffers must be 16-byte aligned");
+  const int r0[3] = {0, 0, 0};
+  Bufs bf;
+  TRY(carve(c, r0, MECEFO_SIDE_INPUT, ws, ws_bytes, &bf));
+  hipStream_t s = (hipStream_t)hip_stream;
+  TRY(recompute_and_dgrad(c, bf, U, desc->ld_act_d, dY, desc->ld_act_d, Wg, Wu, Wd, G, Z, dU, desc->ld_act_d, s));
+  // exact Wgrad: dWg = dG^T U, dWu = dZ^T U [f x d]; dWd = dY^T A [d x f]; contraction over tokens
+  GemmLaunch g = new_launch(c, false, false, EPI_GRAD);
+  g.nprob = 3;
+  g.accumulate = accumulate;
+  const int b = (int)c.b;
+  char* base = bf.base;
+  g.p[0] = prob(base + bf.w.DG, nullptr, c.ldf, U, nullptr, desc->ld_act_d, dWg, nullptr, nullptr, desc->ld_w_fd, c.ff, c.dm, b, 1);
+  g.p[1] = prob(base + bf.w.DZ, nullptr, c.ldf, U, nullptr, desc->ld_act_d, dWu, nullptr, nullptr, desc->ld_w_fd, c.ff, c.dm, b, 1);
+  g.p[2] = prob(dY, nullptr, desc->ld_act_d, base + bf.w.AA, nullptr, c.ldf, dWd, nullptr, nullptr, desc->ld_w_df, c.dm, c.ff, b, 1);
+  HIP_TRY(launch_gemm(g, s));
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_ffn_bwd_lowrank(const mecefo_ffn_desc_t* desc, const void* U, const void* dY,
+                                       const void* Wg, const void* Wu, const void* Wd, mecefo_proj_t Pg,
+                                       mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side, void* dU,
+                                       void* dWg, void* dWu, void* dWd, int accumulate, void* ws,
+                                       size_t ws_bytes, void* hip_stream) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_ptr(c, U, "U", c.b > 0)); TRY(check_ptr(c, dY, "dY", c.b > 0));
+  TRY(check_ptr(c, Wg, "Wg")); TRY(check_ptr(c, Wu, "Wu")); TRY(check_ptr(c, Wd, "Wd"));
+  TRY(check_ptr(c, dU, "dU", false));
+  if (!dWg || !dWu || !dWd) return fail(MECEFO_ERR_INVALID_ARG, "dWg, dWu, dWd are required");
+  if (c.bf16 && (((uintptr_t)dWg | (uintptr_t)dWu | (uintptr_t)dWd) % 16)) return fail(MECEFO_ERR_INVALID_ARG, "gradient buffers must be 16-byte aligned");
+  const mecefo_proj_t P[3] = {Pg, Pu, Pd};
+  TRY(check_lowrank_args(c, P, side));
+  const int r[3] = {Pg.r, Pu.r, Pd.r};
+  Bufs bf;
+  TRY(carve(c, r, side, ws, ws_bytes, &bf));
+  hipStream_t s = (hipStream_t)hip_stream;
+  TRY(recompute_and_dgrad(c, bf, U, desc->ld_act_d, dY, desc->ld_act_d, Wg, Wu, Wd, nullptr, nullptr, dU, desc->ld_act_d, s));
+  void* dW[3] = {dWg, dWu, dWd};
+  return lowrank_wgrad(c, bf, U, desc->ld_act_d, dY, desc->ld_act_d, P, side, dW, accumulate, s);
+}
+
+mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void* H, const void* dOut,
+                                      const void* gamma, const void* Wg, const void* Wu, const void* Wd,
+                                      mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+                                      void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
+                                      void* ws, size_t ws_bytes, void* hip_stream) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_ptr(c, H, "H", c.b > 0)); TRY(check_ptr(c, dOut, "dOut", c.b > 0)); TRY(check_ptr(c, gamma, "gamma", false));
+  TRY(check_ptr(c, Wg, "Wg")); TRY(check_ptr(c, Wu, "Wu")); TRY(check_ptr(c, Wd, "Wd"));
+  TRY(check_ptr(c, dX, "dX", c.b > 0));
+  if (!dWg || !dWu || !dWd) return fail(MECEFO_ERR_INVALID_ARG, "dWg, dWu, dWd are required");
+  if (c.bf16 && (((uintptr_t)dWg | (uintptr_t)dWu | (uintptr_t)dWd) % 16)) return fail(MECEFO_ERR_INVALID_ARG, "gradient buffers must be 16-byte aligned");
+  if (dgamma && !gamma) return fail(MECEFO_ERR_INVALID_ARG, "dgamma requested but gamma is NULL");
+  const mecefo_proj_t P[3] = {Pg, Pu, Pd};
+  TRY(check_lowrank_args(c, P, side));
+  const int r[3] = {Pg.r, Pu.r, Pd.r};
+  Bufs bf;
+  TRY(carve(c, r, side, ws, ws_bytes, &bf));
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* base = bf.base;
+  const void* U = H;
+  int64_t ldu = desc->ld_act_d;
+  float* rstd = (float*)(base + bf.w.rstd);
+  if (gamma && c.b > 0) {  // recompute the norm output from the stored tensor
+    HIP_TRY(launch_rmsnorm_fwd(c.bf16, H, desc->ld_act_d, gamma, desc->rms_eps, base + bf.w.U, c.dm, rstd, c.b, c.dm, s));
+    U = base + bf.w.U;
+    ldu = c.dm;
+  }
+  void* dUb = base + bf.w.dU;
+  TRY(recompute_and_dgrad(c, bf, U, ldu, dOut, desc->ld_act_d, Wg, Wu, Wd, nullptr, nullptr, dUb, c.dm, s));
+  // Eq. (2) reads dOut (as the down projection's output gradient), so it runs before dX may overwrite dOut.
+  void* dW[3] = {dWg, dWu, dWd};
+  TRY(lowrank_wgrad(c, bf, U, ldu, dOut, desc->ld_act_d, P, side, dW, accumulate, s));
+  // Skip the MHA connection: the gradient handed to the previous layer is dH = dOut + normbwd(dU).
+  if (gamma) {
+    const int nblk = rmsnorm_bwd_blocks(c.b);
+    float* dgp = dgamma ? (float*)(base + bf.w.dgp) : nullptr;
+    if (c.b > 0)
+      HIP_TRY(launch_rmsnorm_bwd(c.bf16, dUb, c.dm, H, desc->ld_act_d, rstd, gamma, dOut, desc->ld_act_d, dX,
+                                 desc->ld_act_d, dgp, nblk, c.b, c.dm, s));
+    if (dgamma) HIP_TRY(launch_dgamma_reduce(dgp, c.b > 0 ? nblk : 0, c.dm, dgamma, c.grad_f32, c.bf16, accumulate, s));
+  } else if (c.b > 0) {
+    HIP_TRY(launch_add(c.bf16, dOut, desc->ld_act_d, dUb, c.dm, dX, desc->ld_act_d, c.b, c.dm, s));
+  }
+  return MECEFO_OK;
+}
+
+}  // extern "C"

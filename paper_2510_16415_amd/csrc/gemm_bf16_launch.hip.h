@@ -1,0 +1,66 @@
+// Host-side launch helpers for the bf16 MFMA GEMM instantiations.
+#pragma once
+#include "gemm_bf16.hip.h"
+
+namespace mecefo {
+
+using CfgL = TileCfg<256, 256>;   // large problems: 4 waves x (128 x 128)
+using CfgS = TileCfg<128, 128>;   // small problems: 4 waves x (64 x 64), more blocks
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Total 256x256 tiles of a launch; below this many the 128x128 configuration is used.
+inline int bf16_tiles(const GemmLaunch& g, int bm, int bn) {
+  const bool dual = epi_is_dual(g.epi);
+  int t = 0;
+  for (int i = 0; i < g.nprob; ++i) t += cdiv(g.p[i].M, bm) * cdiv(g.p[i].N, dual ? bn / 2 : bn);
+  return t;
+}
+inline bool bf16_use_large(const GemmLaunch& g) { return bf16_tiles(g, 256, 256) >= 160; }
+
+template <class Cfg, bool AKC, bool BKC, int EPI>
+hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
+  constexpr bool DUAL = epi_is_dual(EPI);
+  KArgs a;
+  a.nprob = g.nprob;
+  int tiles = 0;
+  for (int i = 0; i < 3; ++i) {
+    a.p[i] = g.p[i < g.nprob ? i : 0];
+    a.partial_off[i] = g.partial_off[i];
+    if (i >= g.nprob) continue;
+    GemmProblem& p = a.p[i];
+    p.tiles_m = cdiv(p.M, Cfg::BM);
+    p.tiles_n = cdiv(p.N, DUAL ? Cfg::BN / 2 : Cfg::BN);
+    p.tile_begin = tiles;
+    tiles += p.tiles_m * p.tiles_n;
+    if (p.nseg < 2) { p.A[1] = p.A[0]; if (!DUAL) p.B[1] = p.B[0]; }
+  }
+  a.total_tiles = tiles;
+  a.splits = (EPI == EPI_SPLIT_F32 && g.splits > 1) ? g.splits : 1;
+  a.accumulate = g.accumulate;
+  a.out_f32 = g.out_f32;
+  a.partial = g.partial;
+  if (tiles == 0) return hipSuccess;
+  auto kern = gemm_bf16_kernel<Cfg, AKC, BKC, EPI>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       Cfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(tiles * a.splits), dim3(256), Cfg::LDS_BYTES, stream, a);
+  return hipGetLastError();
+}
+
+template <bool AKC, bool BKC, int EPI>
+hipError_t run_bf16_auto(GemmLaunch& g, hipStream_t stream) {
+  if (bf16_use_large(g)) return run_bf16<CfgL, AKC, BKC, EPI>(g, stream);
+  return run_bf16<CfgS, AKC, BKC, EPI>(g, stream);
+}
+
+hipError_t launch_gemm_bf16_nt(GemmLaunch& g, hipStream_t s);
+hipError_t launch_gemm_bf16_nn(GemmLaunch& g, hipStream_t s);
+hipError_t launch_gemm_bf16_tn(GemmLaunch& g, hipStream_t s);
+
+}  // namespace mecefo

@@ -1,0 +1,11 @@
+// bf16 GEMM instantiations with A K-contiguous and B given as [K x N]: the exact Dgrad
+// products (dY Wd, dG Wg + dZ Wu) and the projection step X P of Eq. (2).
+#include "gemm_bf16_launch.hip.h"
+namespace mecefo {
+hipError_t launch_gemm_bf16_nn(GemmLaunch& g, hipStream_t s) {
+  switch (g.epi) {
+    case EPI_STORE: return run_bf16_auto<true, false, EPI_STORE>(g, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+}  // namespace mecefo

@@ -1,0 +1,14 @@
+// bf16 GEMM instantiations with both operands K-contiguous: FFN recompute (U Wg^T, U Wu^T
+// with SwiGLU epilogues), the down projection, and the expand step C P^T of Eq. (2).
+#include "gemm_bf16_launch.hip.h"
+namespace mecefo {
+hipError_t launch_gemm_bf16_nt(GemmLaunch& g, hipStream_t s) {
+  switch (g.epi) {
+    case EPI_STORE: return run_bf16_auto<true, true, EPI_STORE>(g, s);
+    case EPI_GRAD: return run_bf16_auto<true, true, EPI_GRAD>(g, s);
+    case EPI_SWIGLU_FWD: return run_bf16_auto<true, true, EPI_SWIGLU_FWD>(g, s);
+    case EPI_SWIGLU_BWD: return run_bf16_auto<true, true, EPI_SWIGLU_BWD>(g, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+}  // namespace mecefo

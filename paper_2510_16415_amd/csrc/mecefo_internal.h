@@ -1,0 +1,72 @@
+// Internal host-side interfaces between the C ABI (api.hip) and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mecefo {
+
+enum Epilogue : int {
+  EPI_STORE = 0,       // C0[row, col] = acc                          (activation dtype)
+  EPI_SPLIT_F32 = 1,   // partial[split][row, col] = acc   (fp32 split-K partial, row stride ldc)
+  EPI_GRAD = 2,        // C0[row, col] (+)= acc                       (gradient dtype, optional accumulate)
+  EPI_SWIGLU_FWD = 3,  // dual: G=C0, Z=C1, A=C2 = silu(g)*z
+  EPI_SWIGLU_BWD = 4,  // dual: dA read from C0; C0=dG, C1=dZ, C2=A
+};
+
+// One matrix product C[M x N] = sum over K-segments of opA(A_s) * opB(B_s).
+//   a_kcontig: A_s is [M x K] row-major (K contiguous), else [K x M] (M contiguous).
+//   b_kcontig: B_s is [N x K] row-major (K contiguous), else [K x N] (N contiguous).
+// Dual products (SwiGLU epilogues) use one segment and B[0], B[1] as the gate and up
+// matrices; both products share A and every size.
+struct GemmProblem {
+  const void* A[2];
+  const void* B[2];
+  void* C[3];
+  int64_t lda, ldb, ldc;
+  int M, N, K;
+  int nseg;        // 1 or 2 K segments (ignored for dual products)
+  int pad_cols;    // SwiGLU epilogues: columns [N, pad_cols) of the outputs are set to zero
+  int tile_begin;  // filled by the launcher
+  int tiles_m, tiles_n;
+};
+
+struct GemmLaunch {
+  GemmProblem p[3];
+  int nprob;
+  bool a_kcontig, b_kcontig;
+  int epi;          // Epilogue
+  bool bf16;        // operand dtype (bf16 MFMA path) or fp32
+  bool out_f32;     // EPI_GRAD: gradient buffer dtype is fp32 (else same as operands)
+  int accumulate;   // EPI_GRAD
+  int splits;       // EPI_SPLIT_F32: number of K splits (partials laid out [split][M x ldc] per problem)
+  float* partial;   // EPI_SPLIT_F32: base of the partial buffer; problem i starts at partial_off[i]
+  int64_t partial_off[3];
+};
+
+// Returns hipSuccess or the launch error.  Only enqueues.
+hipError_t launch_gemm(GemmLaunch& g, hipStream_t stream);
+hipError_t launch_gemm_bf16(GemmLaunch& g, hipStream_t stream);
+hipError_t launch_gemm_f32(GemmLaunch& g, hipStream_t stream);
+
+// Elementwise / reduction kernels (elementwise.hip).  `bf16` selects the storage type.
+hipError_t launch_rmsnorm_fwd(bool bf16, const void* H, int64_t ldh, const void* gamma, float eps,
+                              void* U, int64_t ldu, float* rstd, int64_t b, int d, hipStream_t s);
+// dX = dOut + rmsnorm_backward(dU); per-block partial sums of dgamma go to dg_partial [nblk x d].
+hipError_t launch_rmsnorm_bwd(bool bf16, const void* dU, int64_t lddu, const void* H, int64_t ldh,
+                              const float* rstd, const void* gamma, const void* dOut, int64_t lddo,
+                              void* dX, int64_t lddx, float* dg_partial, int nblk, int64_t b, int d,
+                              hipStream_t s);
+int rmsnorm_bwd_blocks(int64_t b);
+hipError_t launch_dgamma_reduce(const float* dg_partial, int nblk, int d, void* dgamma, bool out_f32,
+                                bool bf16, int accumulate, hipStream_t s);
+// dX = dOut + dU  (no-norm variant)
+hipError_t launch_add(bool bf16, const void* a, int64_t lda, const void* bsrc, int64_t ldb, void* out,
+                      int64_t ldo, int64_t rows, int cols, hipStream_t s);
+// C[M x N] (activation dtype) = sum over splits of partial[split][M*N]
+hipError_t launch_splitk_reduce(bool bf16, const float* partial, int splits, int64_t mn, void* C,
+                                hipStream_t s);
+// Standalone SwiGLU backward from saved G, Z: reads dA (in DG), writes DG=dG, DZ=dZ, AA=A; pads zeroed.
+hipError_t launch_swiglu_bwd(bool bf16, const void* G, const void* Z, int64_t ldgz, void* DG, void* DZ,
+                             void* AA, int64_t ldf, int64_t b, int f, int pad_cols, hipStream_t s);
+
+}  // namespace mecefo

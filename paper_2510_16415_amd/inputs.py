@@ -58,15 +58,24 @@ CONFIGS = {
 def round_to_bf16_grid(x: np.ndarray) -> np.ndarray:
     """float32 array -> float32 array whose values are bf16-representable (RNE)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32).astype(np.uint64)
-    lsb = (u >> 16) & 1
-    u = (u + 0x7FFF + lsb) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+    u = x.view(np.uint32).copy()
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    u += np.uint32(0x7FFF)
+    u += lsb                      # finite inputs cannot carry out of the exponent field
+    u &= np.uint32(0xFFFF0000)
+    return u.view(np.float32).reshape(x.shape)
 
 
 def _cast(x: np.ndarray, dtype: str) -> np.ndarray:
-    x = x.astype(np.float32)
+    x = x.astype(np.float32, copy=False)
     return round_to_bf16_grid(x) if dtype == "bf16" else x
+
+
+def _normal(rng: np.random.Generator, shape, std: float = 1.0) -> np.ndarray:
+    x = rng.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        x *= np.float32(std)
+    return x
 
 
 def rng_for(cfg_index: int, *stream: int) -> np.random.Generator:
@@ -76,29 +85,29 @@ def rng_for(cfg_index: int, *stream: int) -> np.random.Generator:
 
 def ffn_weights(rng: np.random.Generator, d: int, f: int, dtype: str, std: float = 0.02):
     """Wg, Wu [f x d], Wd [d x f] ~ N(0, std^2); gamma = 1 (fresh RMSNorm gain)."""
-    Wg = _cast(rng.standard_normal((f, d)) * std, dtype)
-    Wu = _cast(rng.standard_normal((f, d)) * std, dtype)
-    Wd = _cast(rng.standard_normal((d, f)) * std, dtype)
+    Wg = _cast(_normal(rng, (f, d), std), dtype)
+    Wu = _cast(_normal(rng, (f, d), std), dtype)
+    Wd = _cast(_normal(rng, (d, f), std), dtype)
     gamma = np.ones(d, dtype=np.float32)
     return Wg, Wu, Wd, gamma
 
 
 def mha_weights(rng: np.random.Generator, d: int, dtype: str, std: float = 0.02):
     """Wq, Wk, Wv, Wo [d x d] ~ N(0, std^2); attention-norm gain = 1."""
-    Ws = [_cast(rng.standard_normal((d, d)) * std, dtype) for _ in range(4)]
+    Ws = [_cast(_normal(rng, (d, d), std), dtype) for _ in range(4)]
     return (*Ws, np.ones(d, dtype=np.float32))
 
 
 def gaussian_block_io(rng: np.random.Generator, b: int, d: int, dtype: str):
     """Block input / stored FFN input and upstream gradient ~ N(0,1), [b x d] each."""
-    X = _cast(rng.standard_normal((b, d)), dtype)
-    dOut = _cast(rng.standard_normal((b, d)), dtype)
+    X = _cast(_normal(rng, (b, d)), dtype)
+    dOut = _cast(_normal(rng, (b, d)), dtype)
     return X, dOut
 
 
 def perturbed_gain(rng: np.random.Generator, d: int, dtype: str):
     """A non-trivial norm gain (1 + 0.1 N(0,1)) so that tests exercise gamma."""
-    return _cast(1.0 + 0.1 * rng.standard_normal(d), dtype)
+    return _cast(1.0 + 0.1 * _normal(rng, d), dtype)
 
 
 def token_ids(rng: np.random.Generator, batch: int, seq: int) -> np.ndarray:
@@ -110,8 +119,8 @@ def stack_params(cfg: Config, layers: int | None = None):
     L = cfg.layers if layers is None else layers
     d, f = cfg.d_model, cfg.d_ff
     rng = rng_for(cfg.index, 1)
-    emb = _cast(rng.standard_normal((VOCAB, d)) * 0.02, cfg.dtype)
-    lm_head = _cast(rng.standard_normal((VOCAB, d)) * 0.02, cfg.dtype)
+    emb = _cast(_normal(rng, (VOCAB, d), 0.02), cfg.dtype)
+    lm_head = _cast(_normal(rng, (VOCAB, d), 0.02), cfg.dtype)
     blocks = []
     for _ in range(L):
         Wq, Wk, Wv, Wo, g_attn = mha_weights(rng, d, cfg.dtype)
