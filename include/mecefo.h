@@ -121,6 +121,29 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
     void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
     void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Measurement aid (not part of the hot path; the only calls that create HIP objects).
+ * After mecefo_profile_enable(n) every kernel stage enqueued by the calls above is bracketed
+ * by a pair of HIP events on the call's own stream, for at most n stage launches.
+ * mecefo_profile_collect() waits for them, adds elapsed milliseconds and launch counts per
+ * stage into two arrays of MECEFO_STAGE_COUNT entries, and switches timing off again.
+ * Not thread-safe; meant for benchmarks. */
+typedef enum {
+  MECEFO_STAGE_NORM_FWD = 0,       /* RMSNorm recompute from the stored tensor               */
+  MECEFO_STAGE_DGRAD_DOWN = 1,     /* dA = dY Wd                                             */
+  MECEFO_STAGE_RECOMPUTE = 2,      /* G, Z = U Wg^T, U Wu^T with fused SwiGLU backward       */
+  MECEFO_STAGE_SWIGLU_BWD = 3,     /* standalone SwiGLU backward (saved activations given)   */
+  MECEFO_STAGE_DGRAD_GATE_UP = 4,  /* dU = dG Wg + dZ Wu                                     */
+  MECEFO_STAGE_PROJECT = 5,        /* Eq. (2): T = X P (three matrices, one launch)          */
+  MECEFO_STAGE_CONTRACT = 6,       /* Eq. (2): C = Gy^T T over tokens                        */
+  MECEFO_STAGE_SPLITK_REDUCE = 7,  /* sum of the split partials of C                         */
+  MECEFO_STAGE_EXPAND = 8,         /* Eq. (2): dW = C P^T                                    */
+  MECEFO_STAGE_NORM_BWD = 9,       /* dX = dOut + normbwd(dU), dgamma                        */
+  MECEFO_STAGE_WGRAD_EXACT = 10,   /* exact dW = Gy^T X (comparator)                         */
+  MECEFO_STAGE_COUNT = 11
+} mecefo_stage_t;
+mecefo_status_t mecefo_profile_enable(int max_stage_launches);
+mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_stage);
+
 /* Description of the last non-OK status returned on this thread ("" if none). */
 const char* mecefo_last_error(void);
 

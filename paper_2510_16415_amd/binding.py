@@ -56,6 +56,10 @@ def lib() -> C.CDLL:
                                          [C.c_int, _vp, C.c_size_t, _vp])
     L.mecefo_block_bwd_skip.argtypes = ([D] + [_vp] * 6 + [Proj] * 3 + [C.c_int] + [_vp] * 5 +
                                         [C.c_int, _vp, C.c_size_t, _vp])
+    L.mecefo_profile_enable.argtypes = [C.c_int]
+    L.mecefo_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
+    L.mecefo_profile_enable.restype = C.c_int
+    L.mecefo_profile_collect.restype = C.c_int
     for f in ("mecefo_workspace_bytes", "mecefo_ffn_fwd_recompute", "mecefo_ffn_bwd_exact",
               "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip"):
         getattr(L, f).restype = C.c_int
@@ -127,6 +131,23 @@ def mecefo_block_bwd_skip(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX
     _check(lib().mecefo_block_bwd_skip(C.byref(desc), _ptr(H), _ptr(dOut), _ptr(gamma), _ptr(Wg), _ptr(Wu),
                                        _ptr(Wd), Pg, Pu, Pd, int(side), _ptr(dX), _ptr(dgamma), _ptr(dWg),
                                        _ptr(dWu), _ptr(dWd), int(accumulate), p, n, _stream(stream)))
+
+
+STAGES = ["norm_fwd", "dgrad_down", "recompute", "swiglu_bwd", "dgrad_gate_up", "project", "contract",
+          "splitk_reduce", "expand", "norm_bwd", "wgrad_exact"]
+
+
+def mecefo_profile_enable(max_stage_launches: int):
+    _check(lib().mecefo_profile_enable(int(max_stage_launches)))
+
+
+def mecefo_profile_collect():
+    """Returns {stage name: (total milliseconds, launches)} for stages that ran."""
+    n = len(STAGES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int * n)()
+    _check(lib().mecefo_profile_collect(ms, cnt))
+    return {STAGES[i]: (ms[i], cnt[i]) for i in range(n) if cnt[i]}
 
 
 def mecefo_last_error() -> str:

@@ -4,6 +4,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/mecefo.h"
 #include "gemm_bf16_launch.hip.h"
 #include "mecefo_internal.h"
@@ -97,6 +99,33 @@ mecefo_status_t check_proj(const Ctx& c, const mecefo_proj_t& P, int dim, const 
 
 #define TRY(x) do { mecefo_status_t st__ = (x); if (st__ != MECEFO_OK) return st__; } while (0)
 #define HIP_TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return fail(MECEFO_ERR_LAUNCH, "%s: %s", #x, hipGetErrorString(e__)); } while (0)
+
+// ---- optional per-stage timing (measurement only) --------------------------------------
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> ev;     // pairs (start, stop)
+  std::vector<int> stage;
+  size_t used = 0;                // events used
+} g_prof;
+
+struct StageTimer {
+  hipStream_t s;
+  bool active;
+  StageTimer(int stage, hipStream_t stream) : s(stream), active(false) {
+    if (g_prof.on && g_prof.used + 2 <= g_prof.ev.size()) {
+      active = true;
+      g_prof.stage[g_prof.used / 2] = stage;
+      (void)hipEventRecord(g_prof.ev[g_prof.used], s);
+    }
+  }
+  ~StageTimer() {
+    if (active) {
+      (void)hipEventRecord(g_prof.ev[g_prof.used + 1], s);
+      g_prof.used += 2;
+    }
+  }
+};
+#define STAGE(id, stream) StageTimer stage_timer__((id), (stream))
 
 // ---- workspace ------------------------------------------------------------------------
 struct Workspace {
@@ -207,20 +236,24 @@ mecefo_status_t recompute_and_dgrad(const Ctx& c, const Bufs& bf, const void* U,
   const int b = (int)c.b;
   if (b == 0) return MECEFO_OK;
   {  // dA = dY Wd   [b x f], K = d
+    STAGE(MECEFO_STAGE_DGRAD_DOWN, s);
     GemmLaunch g = new_launch(c, true, false, EPI_STORE);
     g.nprob = 1;
     g.p[0] = prob(dY, nullptr, lddy, Wd, nullptr, d.ld_w_df, DG, nullptr, nullptr, c.ldf, b, c.ff, c.dm, 1);
     HIP_TRY(launch_gemm(g, s));
   }
   if (Gsaved) {
+    STAGE(MECEFO_STAGE_SWIGLU_BWD, s);
     HIP_TRY(launch_swiglu_bwd(c.bf16, Gsaved, Zsaved, d.ld_act_f, DG, DZ, AA, c.ldf, c.b, c.ff, (int)c.ldf, s));
   } else {  // G = U Wg^T, Z = U Wu^T with the SwiGLU backward fused into the epilogue
+    STAGE(MECEFO_STAGE_RECOMPUTE, s);
     GemmLaunch g = new_launch(c, true, true, EPI_SWIGLU_BWD);
     g.nprob = 1;
     g.p[0] = prob(U, nullptr, ldu, Wg, Wu, d.ld_w_fd, DG, DZ, AA, c.ldf, b, c.ff, c.dm, 1, (int)c.ldf);
     HIP_TRY(launch_gemm(g, s));
   }
   if (dU) {  // dU = dG Wg + dZ Wu   [b x d], two K segments of length f
+    STAGE(MECEFO_STAGE_DGRAD_GATE_UP, s);
     GemmLaunch g = new_launch(c, true, false, EPI_STORE);
     g.nprob = 1;
     g.p[0] = prob(DG, DZ, c.ldf, Wg, Wu, d.ld_w_fd, dU, nullptr, nullptr, lddu, b, c.dm, c.ff, 2);
@@ -253,6 +286,7 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
   for (int i = 0; i < 3; ++i) { ldt[i] = up(P[i].r, 8); T[i] = base + bf.w.T[i]; C[i] = base + bf.w.C[i]; }
 
   if (b > 0) {  // project: T = (X or Gy) P, contraction over the projected dimension
+    STAGE(MECEFO_STAGE_PROJECT, s);
     GemmLaunch g = new_launch(c, true, false, EPI_STORE);
     g.nprob = 3;
     for (int i = 0; i < 3; ++i)
@@ -274,8 +308,12 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
       g.partial_off[i] = poff;
       poff += (int64_t)splits * rows * ldt[i];
     }
-    HIP_TRY(launch_gemm(g, s));
+    {
+      STAGE(MECEFO_STAGE_CONTRACT, s);
+      HIP_TRY(launch_gemm(g, s));
+    }
     if (splits > 1) {
+      STAGE(MECEFO_STAGE_SPLITK_REDUCE, s);
       // partial of problem i is [split][rows x ldt]; the reduction keeps that row stride
       for (int i = 0; i < 3; ++i) {
         const int rows = in ? m_out[i] : n_in[i];
@@ -284,6 +322,7 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
     }
   }
   {  // expand: dW = C P^T (SIDE_INPUT) or P C^T (SIDE_OUTPUT), K = r, into the gradient buffers
+    STAGE(MECEFO_STAGE_EXPAND, s);
     GemmLaunch g = new_launch(c, true, true, EPI_GRAD);
     g.nprob = 3;
     g.accumulate = accumulate;
@@ -312,6 +351,36 @@ extern "C" {
 
 const char* mecefo_last_error(void) { return g_err; }
 const char* mecefo_version(void) { return "mecefo-gfx950 0.1"; }
+
+mecefo_status_t mecefo_profile_enable(int max_launches) {
+  if (max_launches < 1) return fail(MECEFO_ERR_INVALID_ARG, "max_launches must be >= 1");
+  for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+  g_prof.ev.assign((size_t)max_launches * 2, nullptr);
+  g_prof.stage.assign((size_t)max_launches, 0);
+  for (auto& e : g_prof.ev) HIP_TRY(hipEventCreate(&e));
+  g_prof.used = 0;
+  g_prof.on = true;
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_stage) {
+  if (!ms_by_stage || !launches_by_stage) return fail(MECEFO_ERR_INVALID_ARG, "output arrays are NULL");
+  for (int i = 0; i < MECEFO_STAGE_COUNT; ++i) { ms_by_stage[i] = 0.0; launches_by_stage[i] = 0; }
+  g_prof.on = false;
+  for (size_t i = 0; i + 1 < g_prof.used; i += 2) {
+    HIP_TRY(hipEventSynchronize(g_prof.ev[i + 1]));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, g_prof.ev[i], g_prof.ev[i + 1]));
+    const int st = g_prof.stage[i / 2];
+    ms_by_stage[st] += ms;
+    launches_by_stage[st] += 1;
+  }
+  for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+  g_prof.ev.clear();
+  g_prof.stage.clear();
+  g_prof.used = 0;
+  return MECEFO_OK;
+}
 
 mecefo_status_t mecefo_workspace_bytes(const mecefo_ffn_desc_t* desc, int r_gate, int r_up, int r_down,
                                        size_t* out_bytes) {
@@ -373,6 +442,7 @@ mecefo_status_t mecefo_ffn_bwd_exact(const mecefo_ffn_desc_t* desc, const void* 
   hipStream_t s = (hipStream_t)hip_stream;
   TRY(recompute_and_dgrad(c, bf, U, desc->ld_act_d, dY, desc->ld_act_d, Wg, Wu, Wd, G, Z, dU, desc->ld_act_d, s));
   // exact Wgrad: dWg = dG^T U, dWu = dZ^T U [f x d]; dWd = dY^T A [d x f]; contraction over tokens
+  STAGE(MECEFO_STAGE_WGRAD_EXACT, s);
   GemmLaunch g = new_launch(c, false, false, EPI_GRAD);
   g.nprob = 3;
   g.accumulate = accumulate;
@@ -432,6 +502,7 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
   int64_t ldu = desc->ld_act_d;
   float* rstd = (float*)(base + bf.w.rstd);
   if (gamma && c.b > 0) {  // recompute the norm output from the stored tensor
+    STAGE(MECEFO_STAGE_NORM_FWD, s);
     HIP_TRY(launch_rmsnorm_fwd(c.bf16, H, desc->ld_act_d, gamma, desc->rms_eps, base + bf.w.U, c.dm, rstd, c.b, c.dm, s));
     U = base + bf.w.U;
     ldu = c.dm;
@@ -442,6 +513,7 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
   void* dW[3] = {dWg, dWu, dWd};
   TRY(lowrank_wgrad(c, bf, U, ldu, dOut, desc->ld_act_d, P, side, dW, accumulate, s));
   // Skip the MHA connection: the gradient handed to the previous layer is dH = dOut + normbwd(dU).
+  STAGE(MECEFO_STAGE_NORM_BWD, s);
   if (gamma) {
     const int nblk = rmsnorm_bwd_blocks(c.b);
     float* dgp = dgamma ? (float*)(base + bf.w.dgp) : nullptr;
