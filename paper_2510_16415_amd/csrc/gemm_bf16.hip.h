@@ -1,7 +1,7 @@
 // bf16 MFMA GEMM core for gfx950 (CDNA4): C = opA(A) * opB(B) with fp32 accumulation.
 //
-// One workgroup of 256 threads (four 64-wide wavefronts, 2 x 2) computes a BM x BN tile
-// with v_mfma_f32_32x32x16_bf16.  Operand tiles of BK = 64 are staged through LDS in a
+// One workgroup (WAVES_M x WAVES_N 64-wide wavefronts) computes a BM x BN tile with
+// v_mfma_f32_32x32x16_bf16.  Operand tiles of BK = 64 are staged through LDS in a
 // K-contiguous layout [rows][64] (128 bytes per row) whose 16-byte chunks are XOR-swizzled
 // by row so that the ds_read_b128 of an MFMA operand (32 rows, one chunk) is free of bank
 // conflicts.  Operands that are K-strided in memory (the token-contraction of the weight
@@ -9,6 +9,11 @@
 // way from global memory to LDS, so the inner loop is the same for every layout.
 // Global loads are buffer loads: out-of-range rows / K-tail chunks are turned into zeros
 // by pointing the lane outside the buffer, which costs no branch.
+//
+// Pipeline per K stage: global loads of stage k+1 are issued first; the four K=16 sub-steps
+// run MFMAs on register fragments while the fragments of the next sub-step are fetched from
+// LDS; stage k+1 is written to the other LDS buffer before the last sub-step, whose MFMAs
+// then cover the barrier and the first fragment fetch of the next stage.
 #pragma once
 #include "gemm_common.hip.h"
 
@@ -33,21 +38,24 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
 // next MFMA block of a wave) leaves it unchanged.
 __device__ inline int swz(int row) { return (row ^ ((row >> 3) & 1)) & 7; }
 
-template <int BM_, int BN_>
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
 struct TileCfg {
-  static constexpr int BM = BM_, BN = BN_;
-  static constexpr int WM = BM / 2, WN = BN / 2;     // per-wave tile (2 x 2 waves)
-  static constexpr int TM = WM / 32, TN = WN / 32;   // 32x32 MFMA blocks per wave
+  static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int NT = 64 * WAVES_M * WAVES_N;   // threads per workgroup
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // per-wave tile
+  static constexpr int TM = WM / 32, TN = WN / 32;             // 32x32 MFMA blocks per wave
   static constexpr int A_BYTES = BM * kRowBytes, B_BYTES = BN * kRowBytes;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
 };
 
 // ---- global -> register -> LDS staging of one operand tile (R rows x 64 K) ------------
-// K-contiguous source: thread t owns chunk c = t%8 of rows r0 + 32*i.
-template <int R, bool DUAL>
+// K-contiguous source: thread t owns chunk c = t%8 of rows r0 + RP*i (RP = NT/8 rows per pass).
+template <int R, int NT, bool DUAL>
 struct LoaderKC {
-  static constexpr int NV = R / 32;
+  static constexpr int RP = NT / 8;
+  static constexpr int NV = R / RP;
+  static_assert(NV >= 1 && (!DUAL || NV % 2 == 0), "tile too small for this workgroup");
   u32x4_t v[NV];
   uint32_t voff[NV];
   int c, r0;
@@ -57,20 +65,28 @@ struct LoaderKC {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int ii = DUAL ? (i % (NV / 2)) : i;
-      const int row = row_base + ii * 32 + r0;
+      const int row = row_base + ii * RP + r0;
       voff[i] = row < rows_total ? (uint32_t)(((int64_t)row * ld + c * 8) * 2) : kOOB;
     }
   }
   // k0: first K index of this stage inside the segment; kend: segment length.
-  __device__ inline void load(__amdgpu_buffer_rsrc_t r0s, __amdgpu_buffer_rsrc_t r1s, int k0, int kend) {
+  // `tail` (wave-uniform) says that this stage holds the ragged end of K.
+  __device__ inline void load(__amdgpu_buffer_rsrc_t r0s, __amdgpu_buffer_rsrc_t r1s, int k0, int kend,
+                              bool tail) {
     const int kk = k0 + c * 8;
+    if (!tail) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+        v[i] = __builtin_amdgcn_raw_buffer_load_b128((DUAL && i >= NV / 2) ? r1s : r0s, voff[i], k0 * 2, 0);
+      return;
+    }
     const bool kvalid = kk < kend;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const uint32_t off = kvalid ? voff[i] : kOOB;
       v[i] = __builtin_amdgcn_raw_buffer_load_b128((DUAL && i >= NV / 2) ? r1s : r0s, off, k0 * 2, 0);
     }
-    if (kvalid && kk + 8 > kend) {   // ragged K tail inside a 16-byte chunk: zero it
+    if (kvalid && kk + 8 > kend) {   // ragged K end inside a 16-byte chunk: zero the excess
       const int nvalid = kend - kk;  // 1..7
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
@@ -87,21 +103,23 @@ struct LoaderKC {
   __device__ inline void store(uint8_t* lds) const {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int row = i * 32 + r0;
+      const int row = i * RP + r0;
       *(u32x4_t*)(lds + row * kRowBytes + ((c ^ swz(row)) << 4)) = v[i];
     }
   }
 };
 
-// K-strided source ([K x R], R contiguous): thread t owns an (KB k) x (8 rows) block,
+// K-strided source ([K x R], R contiguous): thread t owns a (KB k) x (8 rows) block,
 // loads KB 16-byte vectors along R, transposes to 8 K-contiguous pieces of KB elements.
-template <int R>
+template <int R, int NT>
 struct LoaderKS {
-  static constexpr int KB = R / 32;          // 8 (R=256) or 4 (R=128)
-  static constexpr int MG = R / 8;
+  static constexpr int MG = R / 8;             // 8-row groups
+  static constexpr int KG = NT / MG;           // K groups
+  static constexpr int KB = kBK / KG;          // K rows per thread: 8, 4 or 2
+  static_assert(KB == 8 || KB == 4 || KB == 2, "unsupported tile / workgroup combination");
   u32x4_t v[KB];
   uint32_t voff;
-  uint32_t ldb2;                             // row stride in bytes
+  uint32_t ldb2;                               // row stride in bytes
   int mg, kg;
   __device__ inline void init(int t, int row_base, int rows_total, int64_t ld) {
     mg = t % MG;
@@ -110,8 +128,14 @@ struct LoaderKS {
     ldb2 = (uint32_t)(ld * 2);
     voff = m < rows_total ? (uint32_t)(((int64_t)(kg * KB) * ld + m) * 2) : kOOB;
   }
-  __device__ inline void load(__amdgpu_buffer_rsrc_t rs, __amdgpu_buffer_rsrc_t, int k0, int kend) {
+  __device__ inline void load(__amdgpu_buffer_rsrc_t rs, __amdgpu_buffer_rsrc_t, int k0, int kend, bool tail) {
     const uint32_t soff = (uint32_t)k0 * ldb2;
+    if (!tail) {
+#pragma unroll
+      for (int kk = 0; kk < KB; ++kk)
+        v[kk] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff == kOOB ? kOOB : voff + kk * ldb2, soff, 0);
+      return;
+    }
 #pragma unroll
     for (int kk = 0; kk < KB; ++kk) {
       const bool kvalid = (k0 + kg * KB + kk) < kend;
@@ -120,7 +144,7 @@ struct LoaderKS {
     }
   }
   __device__ inline void store(uint8_t* lds) const {
-    // in: v[k][j] = (row 2j | row 2j+1 << 16) at K index k.  out for row i: K-contiguous.
+    // in: v[k][j] = (row 2j | row 2j+1 << 16) at K index k.  out for each row: K-contiguous.
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
 #pragma unroll
@@ -133,34 +157,40 @@ struct LoaderKS {
 #pragma unroll
           for (int q = 0; q < 4; ++q) o[q] = __builtin_amdgcn_perm(v[2 * q + 1][j], v[2 * q][j], sel);
           *(u32x4_t*)(dst + ((kg ^ swz(row)) << 4)) = o;
-        } else {
+        } else if constexpr (KB == 4) {
           u32x2_t o;
 #pragma unroll
           for (int q = 0; q < 2; ++q) o[q] = __builtin_amdgcn_perm(v[2 * q + 1][j], v[2 * q][j], sel);
           *(u32x2_t*)(dst + (((kg >> 1) ^ swz(row)) << 4) + ((kg & 1) << 3)) = o;
+        } else {
+          const uint32_t o = __builtin_amdgcn_perm(v[1][j], v[0][j], sel);
+          *(uint32_t*)(dst + (((kg >> 2) ^ swz(row)) << 4) + ((kg & 3) << 2)) = o;
         }
       }
     }
   }
 };
 
-template <int R, bool KC, bool DUAL> struct LoaderSel { using type = LoaderKC<R, DUAL>; };
-template <int R, bool DUAL> struct LoaderSel<R, false, DUAL> {
+template <int R, int NT, bool KC, bool DUAL> struct LoaderSel { using type = LoaderKC<R, NT, DUAL>; };
+template <int R, int NT, bool DUAL> struct LoaderSel<R, NT, false, DUAL> {
   static_assert(!DUAL, "dual products need K-contiguous B");
-  using type = LoaderKS<R>;
+  using type = LoaderKS<R, NT>;
 };
 
-template <class Cfg, bool AKC, bool BKC, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const KArgs args) {
+// DBG (experiments only, 0 in every product instantiation): bit 0 skips the global loads after
+// the first stage, bit 1 also skips the LDS stores, to bound what the memory pipeline costs.
+template <class Cfg, bool AKC, bool BKC, int EPI, int DBG = 0>
+__global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
   constexpr bool DUAL = epi_is_dual(EPI);
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::NT;
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;       // output columns covered per tile
   static_assert(!DUAL || (TN % 2 == 0), "dual tiles pair MFMA blocks");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
   const int t = threadIdx.x;
-  const int lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 
   const int nblocks = args.total_tiles * args.splits;
   const TileCoord tc = map_tile(args, xcd_remap(blockIdx.x, nblocks));
@@ -169,14 +199,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const KArgs args) {
 
   // K range of this block, in stages of 64, over nseg segments each padded to a stage.
   const int nseg = DUAL ? 1 : p.nseg;
-  const int kt_per_seg = (p.K + kBK - 1) / kBK;
+  const int K = p.K;
+  const int kt_per_seg = (K + kBK - 1) / kBK;
   const int kt_total = kt_per_seg * nseg;
-  const int kt_chunk = (kt_total + args.splits - 1) / args.splits;
+  const int kt_chunk = __builtin_amdgcn_readfirstlane((kt_total + args.splits - 1) / args.splits);
   const int kt_begin = tc.split * kt_chunk;
   const int kt_end = min(kt_total, kt_begin + kt_chunk);
 
-  typename LoaderSel<BM, AKC, false>::type la;
-  typename LoaderSel<BN, BKC, DUAL>::type lb;
+  typename LoaderSel<BM, NT, AKC, false>::type la;
+  typename LoaderSel<BN, NT, BKC, DUAL>::type lb;
   la.init(t, m0, p.M, p.lda);
   lb.init(t, n0, p.N, p.ldb);
   const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(p.A[0]);
@@ -196,7 +227,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const KArgs args) {
   const int lrow = lane & 31;
   const int a_row = wm * Cfg::WM + lrow;
   const int a_base = a_row * kRowBytes + ((((lane >> 5) ^ swz(a_row)) & 7) << 4);
-  int b_rowbase[TN];
   int b_base[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
@@ -207,20 +237,36 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const KArgs args) {
     } else {
       row = wn * Cfg::WN + j * 32 + lrow;
     }
-    b_rowbase[j] = row;
     b_base[j] = row * kRowBytes + ((((lane >> 5) ^ swz(row)) & 7) << 4);
   }
 
   auto issue_loads = [&](int kt) {
-    const int seg = kt / kt_per_seg;
+    const int seg = kt >= kt_per_seg ? 1 : 0;
     const int k0 = (kt - seg * kt_per_seg) * kBK;
+    const bool tail = k0 + kBK > K;
     if (DUAL) {
-      la.load(ra0, ra0, k0, p.K);
-      lb.load(rb0, rb1, k0, p.K);
+      la.load(ra0, ra0, k0, K, tail);
+      lb.load(rb0, rb1, k0, K, tail);
     } else {
-      la.load(seg ? ra1 : ra0, ra0, k0, p.K);
-      lb.load(seg ? rb1 : rb0, rb0, k0, p.K);
+      la.load(seg ? ra1 : ra0, ra0, k0, K, tail);
+      lb.load(seg ? rb1 : rb0, rb0, k0, K, tail);
     }
+  };
+
+  bf16x8_t af[2][TM], bfr[2][TN];
+  auto fetch = [&](int slot, const uint8_t* sa, const uint8_t* sb, int ks) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      af[slot][i] = *(const bf16x8_t*)(sa + (a_base ^ (ks << 5)) + i * 32 * kRowBytes);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[slot][j] = *(const bf16x8_t*)(sb + (b_base[j] ^ (ks << 5)));
+  };
+  auto mma = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
   };
 
   if (kt_begin < kt_end) {
@@ -228,38 +274,31 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const KArgs args) {
     la.store(smem);
     lb.store(smem + Cfg::A_BYTES);
     __syncthreads();
+    fetch(0, smem, smem + Cfg::A_BYTES, 0);
     for (int kt = kt_begin; kt < kt_end; ++kt) {
       const int cur = (kt - kt_begin) & 1;
       const uint8_t* sa = smem + cur * Cfg::STAGE_BYTES;
       const uint8_t* sb = sa + Cfg::A_BYTES;
+      uint8_t* na = smem + (cur ^ 1) * Cfg::STAGE_BYTES;
       const bool more = kt + 1 < kt_end;
-      if (more) issue_loads(kt + 1);
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-          af[i] = *(const bf16x8_t*)(sa + (a_base ^ (ks << 5)) + i * 32 * kRowBytes);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          bfr[j] = *(const bf16x8_t*)(sb + (b_base[j] ^ (ks << 5)));
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-      if (more) {
-        uint8_t* na = smem + (cur ^ 1) * Cfg::STAGE_BYTES;
+      if (more && !(DBG & 1)) issue_loads(kt + 1);
+      fetch(1, sa, sb, 1);
+      mma(0);
+      fetch(0, sa, sb, 2);
+      mma(1);
+      fetch(1, sa, sb, 3);
+      mma(0);
+      if (more && !(DBG & 2)) {
         la.store(na);
         lb.store(na + Cfg::A_BYTES);
       }
       __syncthreads();
+      if (more) fetch(0, na, na + Cfg::A_BYTES, 0);
+      mma(1);
     }
   }
 
   // Epilogue.  Accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, col lane%32.
-  (void)b_rowbase;
   const int row_w = m0 + wm * Cfg::WM + 4 * (lane >> 5);
   constexpr int TNO = DUAL ? TN / 2 : TN;
   const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + lrow;

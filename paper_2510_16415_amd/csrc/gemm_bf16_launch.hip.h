@@ -1,11 +1,14 @@
 // Host-side launch helpers for the bf16 MFMA GEMM instantiations.
 #pragma once
-#include "gemm_bf16.hip.h"
+#include <stdlib.h>
+
+#include "gemm_bf16_dtl.hip.h"
 
 namespace mecefo {
 
-using CfgL = TileCfg<256, 256>;   // large problems: 4 waves x (128 x 128)
-using CfgS = TileCfg<128, 128>;   // small problems: 4 waves x (64 x 64), more blocks
+using CfgL4 = TileCfg<256, 256, 2, 2>;   // 4 waves x (128 x 128): fewest LDS reads per MFMA
+using CfgL8 = TileCfg<256, 256, 4, 2>;   // 8 waves x (64 x 128): two waves per SIMD hide latency
+using CfgS = TileCfg<128, 128, 2, 2>;    // small problems: 4 waves x (64 x 64), more blocks
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
@@ -18,7 +21,26 @@ inline int bf16_tiles(const GemmLaunch& g, int bm, int bn) {
 }
 inline bool bf16_use_large(const GemmLaunch& g) { return bf16_tiles(g, 256, 256) >= 160; }
 
-template <class Cfg, bool AKC, bool BKC, int EPI>
+// The direct-to-LDS kernel cannot mask a ragged K inside a 16-byte chunk.
+inline bool bf16_dtl_ok(const GemmLaunch& g) {
+  for (int i = 0; i < g.nprob; ++i)
+    if ((g.a_kcontig || g.b_kcontig) && (g.p[i].K % 8) && !g.p[i].kpad_ok) return false;
+  return true;
+}
+
+// 0: 128x128 / 4 waves, 1: 256x256 / 4 waves, 2: 256x256 / 8 waves (register staging),
+// 3: 256x256 / 8 waves with direct-to-LDS staging.
+// Tuning knob for experiments: MECEFO_TILE = S | L4 | L8R | L8 forces one configuration.
+inline int bf16_tile_choice(const GemmLaunch& g) {
+  static const char* env = getenv("MECEFO_TILE");
+  int c = bf16_use_large(g) ? 3 : 0;
+  if (env && env[0] == 'S') c = 0;
+  if (env && env[0] == 'L') c = env[1] == '4' ? 1 : (env[2] == 'R' ? 2 : 3);
+  if (c == 3 && !bf16_dtl_ok(g)) c = 2;
+  return c;
+}
+
+template <class Cfg, bool AKC, bool BKC, int EPI, bool DTL = false>
 hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
   constexpr bool DUAL = epi_is_dual(EPI);
   KArgs a;
@@ -41,7 +63,9 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
   a.out_f32 = g.out_f32;
   a.partial = g.partial;
   if (tiles == 0) return hipSuccess;
-  auto kern = gemm_bf16_kernel<Cfg, AKC, BKC, EPI>;
+  void (*kern)(const KArgs);
+  if constexpr (DTL) kern = gemm_bf16_dtl_kernel<Cfg, AKC, BKC, EPI>;
+  else kern = gemm_bf16_kernel<Cfg, AKC, BKC, EPI>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -49,14 +73,18 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(tiles * a.splits), dim3(256), Cfg::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL(kern, dim3(tiles * a.splits), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 
 template <bool AKC, bool BKC, int EPI>
 hipError_t run_bf16_auto(GemmLaunch& g, hipStream_t stream) {
-  if (bf16_use_large(g)) return run_bf16<CfgL, AKC, BKC, EPI>(g, stream);
-  return run_bf16<CfgS, AKC, BKC, EPI>(g, stream);
+  switch (bf16_tile_choice(g)) {
+    case 1: return run_bf16<CfgL4, AKC, BKC, EPI>(g, stream);
+    case 2: return run_bf16<CfgL8, AKC, BKC, EPI>(g, stream);
+    case 3: return run_bf16<CfgL8, AKC, BKC, EPI, true>(g, stream);
+    default: return run_bf16<CfgS, AKC, BKC, EPI>(g, stream);
+  }
 }
 
 hipError_t launch_gemm_bf16_nt(GemmLaunch& g, hipStream_t s);

@@ -45,8 +45,12 @@ __device__ inline TileCoord map_tile(const KArgs& a, int bid) {
   const int first_m = g * GROUP;
   const int gm = min(tiles_m - first_m, GROUP);
   const int tt = t - g * gsize;
-  tc.tm = first_m + tt % gm;
-  tc.tn = tt / gm;
+  // Integer division runs on the vector ALU; tell the compiler the results are wave-uniform so
+  // that everything derived from them (buffer offsets, loop bounds) stays in scalar registers.
+  tc.tm = __builtin_amdgcn_readfirstlane(first_m + tt % gm);
+  tc.tn = __builtin_amdgcn_readfirstlane(tt / gm);
+  tc.prob = __builtin_amdgcn_readfirstlane(tc.prob);
+  tc.split = __builtin_amdgcn_readfirstlane(tc.split);
   return tc;
 }
 

@@ -24,13 +24,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const KArgs args, int a_k
   const int nseg = DUAL ? 1 : p.nseg;
   const int kt_per_seg = (p.K + FK - 1) / FK;
   const int kt_total = kt_per_seg * nseg;
-  const int kt_chunk = (kt_total + args.splits - 1) / args.splits;
+  const int kt_chunk = __builtin_amdgcn_readfirstlane((kt_total + args.splits - 1) / args.splits);
   const int kt_begin = tc.split * kt_chunk;
   const int kt_end = min(kt_total, kt_begin + kt_chunk);
 
   float acc[4][4] = {}, acc2[4][4] = {};
   for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const int seg = kt / kt_per_seg;
+    const int seg = kt >= kt_per_seg ? 1 : 0;
     const int k0 = (kt - seg * kt_per_seg) * FK;
     const float* A = (const float*)p.A[DUAL ? 0 : seg];
     // stage A: 64 x 16 elements, 4 per thread

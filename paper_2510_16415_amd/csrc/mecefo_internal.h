@@ -26,6 +26,7 @@ struct GemmProblem {
   int M, N, K;
   int nseg;        // 1 or 2 K segments (ignored for dual products)
   int pad_cols;    // SwiGLU epilogues: columns [N, pad_cols) of the outputs are set to zero
+  int kpad_ok;     // K-contiguous operands: bytes between K and the next multiple of 8 are known to be zero
   int tile_begin;  // filled by the launcher
   int tiles_m, tiles_n;
 };
