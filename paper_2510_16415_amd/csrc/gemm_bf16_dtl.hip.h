@@ -163,6 +163,10 @@ template <int NB> struct FragSel<NB, false> { using type = FragKS<NB>; };
 template <class Cfg, bool AKC, bool BKC, int EPI>
 __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args) {
   constexpr bool DUAL = epi_is_dual(EPI);
+  // fp32 outputs (gradients, split-K partials): issue the MFMA with swapped operands so that a
+  // lane holds four consecutive columns and stores 16 bytes; bf16 outputs keep the layout in
+  // which a half-wave writes 32 consecutive columns of one row.
+  constexpr bool SWAP = EPI == EPI_GRAD || EPI == EPI_SPLIT_F32;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::NT;
   static_assert(BM == 256 && BN == 256 && NT == 512, "direct-to-LDS path is built for 256x256 tiles, 8 waves");
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;
@@ -236,7 +240,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0)
+                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
   };
 
   if (kt_begin < kt_end) {
@@ -272,21 +277,45 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
     }
   }
 
+  // Epilogue.  Accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, col lane%32.
+  if constexpr (!SWAP) {
+    const int row_w = m0 + wm * Cfg::WM + 4 * (lane >> 5);
+    constexpr int TNO = DUAL ? TN / 2 : TN;
+    const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TNO; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = row_w + i * 32 + 8 * (e >> 2) + (e & 3);
+          const int col = col_w + j * 32;
+          const float v = acc[i][j][e];
+          const float v2 = DUAL ? acc[i][DUAL ? j + TN / 2 : j][e] : 0.f;
+          epilogue_elem<EPI, __bf16>(p, args, tc.prob, tc.split, row, col, v, v2);
+        }
+    return;
+  }
+  // Swapped operands: the B fragment was the MFMA's row operand, so a lane holds, for
+  // block (i, j), output row lane%32 and the four consecutive columns 8*g + 4*(lane/32) + 0..3
+  // in accumulator elements 4g..4g+3 (g = 0..3): stores are 8 or 16 bytes wide.
   const int lrow = lane & 31;
-  const int row_w = m0 + wm * Cfg::WM + 4 * (lane >> 5);
+  const int row_w = m0 + wm * Cfg::WM + lrow;
   constexpr int TNO = DUAL ? TN / 2 : TN;
-  const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + lrow;
+  const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TNO; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = row_w + i * 32 + 8 * (e >> 2) + (e & 3);
-        const int col = col_w + j * 32;
-        const float v = acc[i][j][e];
-        const float v2 = DUAL ? acc[i][DUAL ? j + TN / 2 : j][e] : 0.f;
-        epilogue_elem<EPI, __bf16>(p, args, tc.prob, tc.split, row, col, v, v2);
+      for (int g4 = 0; g4 < 4; ++g4) {
+        float v[4], v2[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = acc[i][j][4 * g4 + e];
+          v2[e] = DUAL ? acc[i][DUAL ? j + TN / 2 : j][4 * g4 + e] : 0.f;
+        }
+        epilogue_vec4<EPI>(p, args, tc.prob, tc.split, row_w + i * 32, col_w + j * 32 + 8 * g4, v, v2);
       }
 }
 

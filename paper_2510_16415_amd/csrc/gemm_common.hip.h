@@ -14,7 +14,33 @@ struct KArgs {
   int out_f32;
   float* partial;
   int64_t partial_off[3];
+  // Schedule (filled by fill_schedule): the logical tile order is eight consecutive segments, one
+  // per XCD; segment x lists, heaviest problem first, the x-th eighth of every problem's tiles.
+  int order[3];         // problem indices, most work per tile first
+  int lstart[8][3];     // logical index at which (segment x, slot s) starts
+  int tstart[8][3];     // first tile (within its problem) of that chunk
 };
+
+// Host side: tile_begin / tiles_m / tiles_n must be set.  Longest-processing-time-first inside each
+// XCD segment keeps the tail of a grouped launch short when the problems differ in K.
+inline void fill_schedule(KArgs& a) {
+  int idx[3] = {0, 1, 2};
+  auto work = [&](int i) { return i < a.nprob ? (int64_t)a.p[i].K * (a.p[i].nseg > 1 ? 2 : 1) : (int64_t)-1; };
+  for (int i = 0; i < 3; ++i)
+    for (int j = i + 1; j < 3; ++j)
+      if (work(idx[j]) > work(idx[i])) { int t = idx[i]; idx[i] = idx[j]; idx[j] = t; }
+  int l = 0;
+  for (int s = 0; s < 3; ++s) a.order[s] = idx[s];
+  for (int x = 0; x < 8; ++x)
+    for (int s = 0; s < 3; ++s) {
+      const int pi = idx[s];
+      const int T = pi < a.nprob ? a.p[pi].tiles_m * a.p[pi].tiles_n : 0;
+      const int b0 = (int)((int64_t)x * T / 8), b1 = (int)((int64_t)(x + 1) * T / 8);
+      a.lstart[x][s] = l;
+      a.tstart[x][s] = b0;
+      l += b1 - b0;
+    }
+}
 
 // The hardware hands consecutive workgroup ids to the 8 XCDs round-robin.  Renumber so
 // that each XCD works on one contiguous range of logical ids: neighbouring tiles (which
@@ -31,13 +57,18 @@ struct TileCoord { int prob, tm, tn, split; };
 // running blocks reuse both A panels (same tile-row) and B panels (same tile-column).
 __device__ inline TileCoord map_tile(const KArgs& a, int bid) {
   TileCoord tc;
-  tc.split = bid / a.total_tiles;
-  int t = bid - tc.split * a.total_tiles;
-  int pi = 0;
-  if (a.nprob > 1 && t >= a.p[1].tile_begin) pi = 1;
-  if (a.nprob > 2 && t >= a.p[2].tile_begin) pi = 2;
+  tc.split = __builtin_amdgcn_readfirstlane(bid / a.total_tiles);
+  const int l = __builtin_amdgcn_readfirstlane(bid - tc.split * a.total_tiles);
+  // find the (segment, slot) chunk that holds logical index l: the last one starting at or before l
+  int x = 0, sl = 0;
+#pragma unroll
+  for (int xi = 0; xi < 8; ++xi)
+#pragma unroll
+    for (int si = 0; si < 3; ++si)
+      if (a.lstart[xi][si] <= l) { x = xi; sl = si; }
+  const int pi = a.order[sl];
   tc.prob = pi;
-  t -= a.p[pi].tile_begin;
+  int t = l - a.lstart[x][sl] + a.tstart[x][sl];
   const int tiles_m = a.p[pi].tiles_m, tiles_n = a.p[pi].tiles_n;
   constexpr int GROUP = 8;
   const int gsize = GROUP * tiles_n;
@@ -125,5 +156,74 @@ __device__ inline void epilogue_elem(const GemmProblem& p, const KArgs& a, int p
 }
 
 constexpr bool epi_is_dual(int epi) { return epi == EPI_SWIGLU_FWD || epi == EPI_SWIGLU_BWD; }
+
+// Four consecutive output columns of one row (bf16 storage path): 8-byte stores of bf16 and
+// 16-byte stores of fp32 when the group lies inside the matrix, else element by element.
+// Row strides are multiples of 8 elements and col0 of 4, so the vector accesses are aligned.
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ inline bf16x4_t pack_bf16x4(float a, float b, float c, float d) {
+  bf16x4_t o;
+  o[0] = (__bf16)a; o[1] = (__bf16)b; o[2] = (__bf16)c; o[3] = (__bf16)d;
+  return o;
+}
+
+template <int EPI>
+__device__ inline void epilogue_vec4(const GemmProblem& p, const KArgs& a, int prob, int split, int row,
+                                     int col0, const float (&v)[4], const float (&v2)[4]) {
+  if (row >= p.M) return;
+  if (col0 + 4 > p.N) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) epilogue_elem<EPI, __bf16>(p, a, prob, split, row, col0 + e, v[e], v2[e]);
+    return;
+  }
+  const int64_t idx = (int64_t)row * p.ldc + col0;
+  if constexpr (EPI == EPI_STORE) {
+    *(bf16x4_t*)((__bf16*)p.C[0] + idx) = pack_bf16x4(v[0], v[1], v[2], v[3]);
+  } else if constexpr (EPI == EPI_SPLIT_F32) {
+    float* base = a.partial + a.partial_off[prob] + (int64_t)split * p.M * p.ldc;
+    f32x4_t o = {v[0], v[1], v[2], v[3]};
+    *(f32x4_t*)(base + idx) = o;
+  } else if constexpr (EPI == EPI_GRAD) {
+    if (a.out_f32) {
+      f32x4_t* c = (f32x4_t*)((float*)p.C[0] + idx);
+      f32x4_t o = {v[0], v[1], v[2], v[3]};
+      if (a.accumulate) o += *c;
+      *c = o;
+    } else {
+      bf16x4_t* c = (bf16x4_t*)((__bf16*)p.C[0] + idx);
+      if (a.accumulate) {
+        const bf16x4_t old = *c;
+        *c = pack_bf16x4(v[0] + (float)old[0], v[1] + (float)old[1], v[2] + (float)old[2], v[3] + (float)old[3]);
+      } else {
+        *c = pack_bf16x4(v[0], v[1], v[2], v[3]);
+      }
+    }
+  } else if constexpr (EPI == EPI_SWIGLU_FWD) {
+    float av[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) av[e] = v[e] * sigmoid_f<false>(v[e]) * v2[e];
+    if (p.C[0]) *(bf16x4_t*)((__bf16*)p.C[0] + idx) = pack_bf16x4(v[0], v[1], v[2], v[3]);
+    if (p.C[1]) *(bf16x4_t*)((__bf16*)p.C[1] + idx) = pack_bf16x4(v2[0], v2[1], v2[2], v2[3]);
+    *(bf16x4_t*)((__bf16*)p.C[2] + idx) = pack_bf16x4(av[0], av[1], av[2], av[3]);
+  } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+    bf16x4_t* dg = (bf16x4_t*)((__bf16*)p.C[0] + idx);
+    const bf16x4_t da4 = *dg;
+    float oa[4], oz[4], og[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float da = (float)da4[e];
+      const float sg = sigmoid_f<false>(v[e]);
+      const float s = v[e] * sg;
+      oa[e] = s * v2[e];
+      oz[e] = da * s;
+      og[e] = da * v2[e] * (sg * (1.0f + v[e] * (1.0f - sg)));
+    }
+    *(bf16x4_t*)((__bf16*)p.C[2] + idx) = pack_bf16x4(oa[0], oa[1], oa[2], oa[3]);
+    *(bf16x4_t*)((__bf16*)p.C[1] + idx) = pack_bf16x4(oz[0], oz[1], oz[2], oz[3]);
+    *dg = pack_bf16x4(og[0], og[1], og[2], og[3]);
+  }
+}
 
 }  // namespace mecefo

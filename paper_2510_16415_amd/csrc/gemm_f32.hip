@@ -105,6 +105,7 @@ hipError_t run_f32(GemmLaunch& g, hipStream_t stream) {
     if (p.nseg < 2) { p.A[1] = p.A[0]; if (!epi_is_dual(EPI)) p.B[1] = p.B[0]; }
   }
   a.total_tiles = tiles;
+  fill_schedule(a);
   a.splits = (EPI == EPI_SPLIT_F32 && g.splits > 1) ? g.splits : 1;
   a.accumulate = g.accumulate;
   a.out_f32 = 1;
