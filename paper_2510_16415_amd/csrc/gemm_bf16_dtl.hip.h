@@ -1,10 +1,12 @@
 // bf16 MFMA GEMM for gfx950 with direct-to-LDS operand staging.
 //
-// Same tiling and inner loop as gemm_bf16.hip.h (256 x 256 x 64 stages, eight wavefronts of
-// 64 x 128, v_mfma_f32_32x32x16_bf16), but the operand tiles never pass through registers:
+// Same tiling as gemm_bf16.hip.h (256 x 256 output tile, eight wavefronts of 64 x 128,
+// v_mfma_f32_32x32x16_bf16), but the operand tiles never pass through registers:
 // `buffer_load_dwordx4 ... lds` writes 1 KiB per wavefront instruction straight into LDS
-// (lane i lands at base + 16 i), and a stage is refilled as soon as the barrier that ends
-// its last use has passed, one full stage ahead of its first use.
+// (lane i lands at base + 16 i).  K is cut into stages of BK (32 or 64) held in a ring of NS
+// LDS buffers; a buffer is refilled as soon as the barrier that ends its last use has passed,
+// NS - 1 stages ahead of its next use, and the kernel waits (vmcnt) only for the stage it is
+// about to read, leaving the younger fills in flight.
 //   * K-contiguous operands keep the XOR-swizzled [rows][64] layout: the swizzle is applied by
 //     choosing which 16-byte chunk of the row each lane fetches.
 //   * K-strided operands ([K x rows] in memory: weights used as [K x N], activations in the
@@ -44,23 +46,37 @@ __device__ inline void fill_lds_16B(u32x4_t rsrc, uint32_t lds_addr, uint32_t vo
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
-__device__ inline void wait_fills() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Wait until at most `stages_left` younger stages (FPS fill instructions each, per wave) are in flight.
+template <int FPS>
+__device__ inline void wait_fills_leave(int stages_left) {
+  if (stages_left <= 0) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(0) : "memory");
+  else if (stages_left == 1) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(FPS) : "memory");
+  else if (stages_left == 2) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * FPS) : "memory");
+  else asm volatile("s_waitcnt vmcnt(%0)" :: "n"(3 * FPS) : "memory");
+}
 
-// ---- direct-to-LDS fill of one operand tile (256 rows x 64 K = 32 KiB, 32 wave instructions) ----
-template <int NT, bool DUAL>
-struct DmaKC {   // K-contiguous source; wave instruction g covers rows 8g..8g+7 (128 bytes each)
-  static constexpr int NW = NT / 64, NI = 32 / NW;
+// ---- direct-to-LDS fill of one operand tile (256 rows x BK) --------------------------------
+// Swizzle of the K-contiguous layout [rows][BK]: physical 16-byte chunk = logical ^ kc_swz(row).
+template <int BK> __device__ inline int kc_swz(int row) {
+  if constexpr (BK == 64) return swz(row);                 // 8 chunks per 128-byte row
+  else return ((row >> 1) ^ (row >> 3)) & 3;               // 4 chunks per 64-byte row
+}
+
+template <int BK, int NT, bool DUAL>
+struct DmaKC {   // K-contiguous source; one wave instruction covers RPI consecutive rows
+  static constexpr int ROWB = BK * 2, CH = ROWB / 16, RPI = 1024 / ROWB;
+  static constexpr int NW = NT / 64, NI = (256 / RPI) / NW;
+  static_assert(NI >= 1 && (!DUAL || NI % 2 == 0), "unsupported stage size");
   uint32_t voff[NI];
-  int c;       // logical 16-byte chunk this lane fetches (same for all its instructions)
+  int c;       // logical 16-byte chunk this lane fetches (the same for all its instructions)
   int w;
   __device__ inline void init(int lane, int wave, int row_base, int rows_total, int64_t ld) {
     w = wave;
-    const int rsub = lane >> 3;
-    // swz(row) for row = 8g + rsub, g = q*NW + w: depends on rsub and the parity of w only
-    c = (lane & 7) ^ ((rsub ^ (w & 1)) & 7);
+    const int rsub = lane / CH;
+    c = (lane % CH) ^ kc_swz<BK>(w * RPI + rsub);   // instructions q*NW + w differ by multiples of 64 rows
 #pragma unroll
     for (int q = 0; q < NI; ++q) {
-      const int row = (q * NW + w) * 8 + rsub;
+      const int row = (q * NW + w) * RPI + rsub;
       const int gr = row_base + (DUAL ? (row & 127) : row);
       voff[q] = gr < rows_total ? (uint32_t)(((int64_t)gr * ld + c * 8) * 2) : kOOB;
     }
@@ -77,9 +93,10 @@ struct DmaKC {   // K-contiguous source; wave instruction g covers rows 8g..8g+7
 
 __device__ inline int ks_swz(int k) { return (k & 7) << 1; }   // XOR on the 16-byte chunk index
 
-template <int NT>
+template <int BK, int NT>
 struct DmaKS {   // K-strided source; wave instruction g covers k rows 2g, 2g+1 (512 bytes each)
-  static constexpr int NW = NT / 64, NI = 32 / NW;
+  static constexpr int NW = NT / 64, NI = (BK / 2) / NW;
+  static_assert(NI >= 1 && NW == 8, "unsupported stage size");
   uint32_t voff;      // lane offset for q = 0; instruction q adds 2*NW*q rows
   uint32_t ld2;
   int krow0;          // k row of this lane for q = 0
@@ -87,7 +104,7 @@ struct DmaKS {   // K-strided source; wave instruction g covers k rows 2g, 2g+1 
   __device__ inline void init(int lane, int wave, int row_base, int rows_total, int64_t ld) {
     w = wave;
     krow0 = 2 * w + (lane >> 5);
-    const int cm = (lane & 31) ^ ks_swz(krow0);     // rows 2*NW*q apart share k & 7 (NW = 8)
+    const int cm = (lane & 31) ^ ks_swz(krow0);     // rows 16 q apart share k & 7
     const int m = row_base + cm * 8;
     ld2 = (uint32_t)(ld * 2);
     voff = m < rows_total ? (uint32_t)(((int64_t)krow0 * ld + m) * 2) : kOOB;
@@ -103,15 +120,15 @@ struct DmaKS {   // K-strided source; wave instruction g covers k rows 2g, 2g+1 
   }
 };
 
-template <int NT, bool KC, bool DUAL> struct DmaSel { using type = DmaKC<NT, DUAL>; };
-template <int NT, bool DUAL> struct DmaSel<NT, false, DUAL> {
+template <int BK, int NT, bool KC, bool DUAL> struct DmaSel { using type = DmaKC<BK, NT, DUAL>; };
+template <int BK, int NT, bool DUAL> struct DmaSel<BK, NT, false, DUAL> {
   static_assert(!DUAL, "dual products need K-contiguous B");
-  using type = DmaKS<NT>;
+  using type = DmaKS<BK, NT>;
 };
 
 // ---- MFMA operand fetch from LDS ------------------------------------------------------
 // NB blocks of 32 rows.  K-contiguous tiles: one ds_read_b128 per block and K sub-step.
-template <int NB>
+template <int BK, int NB>
 struct FragKC {
   int base[NB];
   // rows[i]: first tile row of block i for this wave
@@ -119,7 +136,7 @@ struct FragKC {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       const int row = rows[i] + (lane & 31);
-      base[i] = row * kRowBytes + ((((lane >> 5) ^ swz(row)) & 7) << 4);
+      base[i] = row * (BK * 2) + (((lane >> 5) ^ kc_swz<BK>(row)) << 4);
     }
   }
   __device__ inline void fetch(bf16x8_t (&f)[NB], const uint8_t* tile, int ks) const {
@@ -128,8 +145,8 @@ struct FragKC {
   }
 };
 
-// K-strided tiles ([64 k][256 rows], 512 bytes per k): two transposing 8-byte reads per block.
-template <int NB>
+// K-strided tiles ([BK k][256 rows], 512 bytes per k): two transposing 8-byte reads per block.
+template <int BK, int NB>
 struct FragKS {
   int base[NB][2];
   __device__ inline void init(int lane, const int (&rows)[NB]) {
@@ -157,17 +174,30 @@ struct FragKS {
   }
 };
 
-template <int NB, bool KC> struct FragSel { using type = FragKC<NB>; };
-template <int NB> struct FragSel<NB, false> { using type = FragKS<NB>; };
+template <int BK, int NB, bool KC> struct FragSel { using type = FragKC<BK, NB>; };
+template <int BK, int NB> struct FragSel<BK, NB, false> { using type = FragKS<BK, NB>; };
 
-template <class Cfg, bool AKC, bool BKC, int EPI>
+// Pipeline shape of the direct-to-LDS kernel: K elements per stage and number of LDS buffers.
+template <int BK_, int NS_> struct DtlPipe {
+  static constexpr int BK = BK_, NS = NS_;
+  static constexpr int A_BYTES = 256 * BK * 2, STAGE_BYTES = 2 * A_BYTES;
+  // per-wave LDS slice of the staged epilogue: 32 rows x (128 + 8) floats, or 2 x 32 x (64 + 8)
+  static constexpr int EP_WAVE_BYTES = 2 * 32 * 72 * 4;
+  static constexpr int LDS_BYTES = NS * STAGE_BYTES > 8 * EP_WAVE_BYTES ? NS * STAGE_BYTES : 8 * EP_WAVE_BYTES;
+  static_assert(NS >= 2 && NS <= 4 && (BK == 32 || BK == 64) && LDS_BYTES <= 160 * 1024, "bad pipeline");
+  static_assert(32 * 136 * 4 <= EP_WAVE_BYTES, "epilogue slice too small");
+};
+
+// DBG (experiments only, 0 in every product instantiation): bit 0 skips the refills, bit 1 makes
+// every refill fetch K offset 0 (cache-resident), bit 2 skips the B refills, bit 3 skips the
+// fragment fetches and MFMAs (fill traffic only).
+template <class Cfg, class Pipe, bool AKC, bool BKC, int EPI, int DBG = 0>
 __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args) {
   constexpr bool DUAL = epi_is_dual(EPI);
-  // fp32 outputs (gradients, split-K partials): issue the MFMA with swapped operands so that a
-  // lane holds four consecutive columns and stores 16 bytes; bf16 outputs keep the layout in
-  // which a half-wave writes 32 consecutive columns of one row.
-  constexpr bool SWAP = EPI == EPI_GRAD || EPI == EPI_SPLIT_F32;
+  constexpr bool SWAP = false;   // every epilogue of this kernel is staged through LDS
   constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::NT;
+  constexpr int BK = Pipe::BK, NS = Pipe::NS, KS = BK / 16, FPS = BK / 8;
+  constexpr int A_BYTES = Pipe::A_BYTES, STAGE = Pipe::STAGE_BYTES;
   static_assert(BM == 256 && BN == 256 && NT == 512, "direct-to-LDS path is built for 256x256 tiles, 8 waves");
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -184,14 +214,14 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
 
   const int nseg = DUAL ? 1 : p.nseg;
   const int K = p.K;
-  const int kt_per_seg = (K + kBK - 1) / kBK;
+  const int kt_per_seg = (K + BK - 1) / BK;
   const int kt_total = kt_per_seg * nseg;
   const int kt_chunk = __builtin_amdgcn_readfirstlane((kt_total + args.splits - 1) / args.splits);
   const int kt_begin = tc.split * kt_chunk;
   const int kt_end = min(kt_total, kt_begin + kt_chunk);
 
-  typename DmaSel<NT, AKC, false>::type da;
-  typename DmaSel<NT, BKC, DUAL>::type db;
+  typename DmaSel<BK, NT, AKC, false>::type da;
+  typename DmaSel<BK, NT, BKC, DUAL>::type db;
   da.init(lane, wave, m0, p.M, p.lda);
   db.init(lane, wave, n0, p.N, p.ldb);
   const u32x4_t ra0 = make_rsrc_words(p.A[0]);
@@ -208,8 +238,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
     if constexpr (DUAL) b_rows[j] = (j >= TN / 2 ? BN / 2 : 0) + wn * (Cfg::WN / 2) + (j % (TN / 2)) * 32;
     else b_rows[j] = wn * Cfg::WN + j * 32;
   }
-  typename FragSel<TM, AKC>::type fa;
-  typename FragSel<TN, BKC>::type fb;
+  typename FragSel<BK, TM, AKC>::type fa;
+  typename FragSel<BK, TN, BKC>::type fb;
   fa.init(lane, a_rows);
   fb.init(lane, b_rows);
 
@@ -223,14 +253,14 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
 
   auto issue = [&](int kt, uint32_t stage) {
     const int seg = kt >= kt_per_seg ? 1 : 0;
-    const int k0 = (kt - seg * kt_per_seg) * kBK;
-    const bool tail = k0 + kBK > K;
+    const int k0 = (DBG & 2) ? 0 : (kt - seg * kt_per_seg) * BK;
+    const bool tail = k0 + BK > K;
     if (DUAL) {
       da.issue(ra0, ra0, stage, k0, K, tail);
-      db.issue(rb0, rb1, stage + Cfg::A_BYTES, k0, K, tail);
+      db.issue(rb0, rb1, stage + A_BYTES, k0, K, tail);
     } else {
       da.issue(seg ? ra1 : ra0, ra0, stage, k0, K, tail);
-      db.issue(seg ? rb1 : rb0, rb0, stage + Cfg::A_BYTES, k0, K, tail);
+      if (!(DBG & 4)) db.issue(seg ? rb1 : rb0, rb0, stage + A_BYTES, k0, K, tail);
     }
   };
 
@@ -244,56 +274,85 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
   };
 
-  if (kt_begin < kt_end) {
-    issue(kt_begin, smem_addr);
-    wait_fills();
+  const int nst = kt_end - kt_begin;
+  if (nst > 0) {
+    // Fill every buffer of the ring, wait for the first stage only.
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      if (s < nst) issue(kt_begin + s, smem_addr + s * STAGE);
+    wait_fills_leave<FPS>(min(NS, nst) - 1);
     __syncthreads();
-    if (kt_begin + 1 < kt_end) issue(kt_begin + 1, smem_addr + Cfg::STAGE_BYTES);
     fa.fetch(af[0], smem, 0);
-    fb.fetch(bfr[0], smem + Cfg::A_BYTES, 0);
+    fb.fetch(bfr[0], smem + A_BYTES, 0);
+    int buf = 0;
     for (int kt = kt_begin; kt < kt_end; ++kt) {
-      const int cur = (kt - kt_begin) & 1;
-      uint8_t* sc = smem + cur * Cfg::STAGE_BYTES;
-      uint8_t* sn = smem + (cur ^ 1) * Cfg::STAGE_BYTES;
-      fa.fetch(af[1], sc, 1);
-      fb.fetch(bfr[1], sc + Cfg::A_BYTES, 1);
-      mma(0);
-      fa.fetch(af[0], sc, 2);
-      fb.fetch(bfr[0], sc + Cfg::A_BYTES, 2);
-      mma(1);
-      fa.fetch(af[1], sc, 3);
-      fb.fetch(bfr[1], sc + Cfg::A_BYTES, 3);
-      mma(0);
-      // Every fragment of stage `cur` is in registers and stage `cur^1` has been filling for a
-      // whole stage: wait for both, then refill `cur` with the stage after next.
-      wait_fills();
-      __syncthreads();
-      if (kt + 2 < kt_end) issue(kt + 2, smem_addr + cur * Cfg::STAGE_BYTES);
-      if (kt + 1 < kt_end) {
-        fa.fetch(af[0], sn, 0);
-        fb.fetch(bfr[0], sn + Cfg::A_BYTES, 0);
+      const uint8_t* sc = smem + buf * STAGE;
+      const int nbuf = buf + 1 == NS ? 0 : buf + 1;
+#pragma unroll
+      for (int ks = 0; ks + 1 < KS; ++ks) {
+        if (DBG & 8) break;
+        fa.fetch(af[(ks + 1) & 1], sc, ks + 1);
+        fb.fetch(bfr[(ks + 1) & 1], sc + A_BYTES, ks + 1);
+        mma(ks & 1);
       }
-      mma(1);
+      // Every fragment of this stage is in registers.  Wait for the next stage only (younger
+      // fills stay in flight), meet the other waves, then refill this buffer NS stages ahead.
+      wait_fills_leave<FPS>(min(NS - 2, kt_end - kt - 2));
+      __syncthreads();
+      if (kt + NS < kt_end && !(DBG & 1)) issue(kt + NS, smem_addr + buf * STAGE);
+      if (kt + 1 < kt_end && !(DBG & 8)) {
+        fa.fetch(af[0], smem + nbuf * STAGE, 0);
+        fb.fetch(bfr[0], smem + nbuf * STAGE + A_BYTES, 0);
+      }
+      if (!(DBG & 8)) mma((KS - 1) & 1);
+      buf = nbuf;
     }
   }
 
-  // Epilogue.  Accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, col lane%32.
+  // Epilogue, staged through LDS so that global accesses are 16 bytes per lane and cover whole
+  // rows (bf16: eight columns per access, fp32: two accesses of four).  Accumulator element e of a 32x32 block sits at row
+  // 8*(e/4) + 4*(lane/32) + e%4, column lane%32; each wave writes 32 rows of its sub-tile as fp32
+  // into its own LDS slice (row stride RS floats, chosen so that the two half-waves hit
+  // different banks), then reads rows back eight columns per lane.  The operand stages are
+  // free at this point: the loop's last barrier followed every fragment fetch and every fill.
   if constexpr (!SWAP) {
-    const int row_w = m0 + wm * Cfg::WM + 4 * (lane >> 5);
     constexpr int TNO = DUAL ? TN / 2 : TN;
-    const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + (lane & 31);
+    constexpr int W = TNO * 32;                 // columns per matrix in this wave's sub-tile
+    constexpr int RS = W + 8;                   // 4*RS % 64 == 32
+    constexpr int MAT = 32 * RS;                // floats per staged matrix
+    float* ep = (float*)(smem + wave * Pipe::EP_WAVE_BYTES);
+    const int wr_off = (4 * (lane >> 5)) * RS + (lane & 31);
+    constexpr int LPR = W / 8;                  // lanes per row when reading back
+    constexpr int RPI = 64 / LPR;               // rows per read instruction
+    const int rd_row = lane / LPR, rd_c8 = (lane % LPR) * 8;
+    const int row_w = m0 + wm * Cfg::WM;
+    const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + rd_c8;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int j = 0; j < TNO; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int row = row_w + i * 32 + 8 * (e >> 2) + (e & 3);
-          const int col = col_w + j * 32;
-          const float v = acc[i][j][e];
-          const float v2 = DUAL ? acc[i][DUAL ? j + TN / 2 : j][e] : 0.f;
-          epilogue_elem<EPI, __bf16>(p, args, tc.prob, tc.split, row, col, v, v2);
+          const int o = wr_off + (8 * (e >> 2) + (e & 3)) * RS + j * 32;
+          ep[o] = acc[i][j][e];
+          if constexpr (DUAL) ep[MAT + o] = acc[i][j + TN / 2][e];
         }
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int rl = it * RPI + rd_row;
+        const float* src = ep + rl * RS + rd_c8;
+        float v[8], v2[8];
+        const f32x4_t g0 = *(const f32x4_t*)src, g1 = *(const f32x4_t*)(src + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[e] = g0[e]; v[4 + e] = g1[e]; v2[e] = 0.f; v2[4 + e] = 0.f; }
+        if constexpr (DUAL) {
+          const f32x4_t z0 = *(const f32x4_t*)(src + MAT), z1 = *(const f32x4_t*)(src + MAT + 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { v2[e] = z0[e]; v2[4 + e] = z1[e]; }
+        }
+        epilogue_vec8<EPI>(p, args, tc.prob, tc.split, row_w + i * 32 + rl, col_w, v, v2);
+      }
+    }
     return;
   }
   // Swapped operands: the B fragment was the MFMA's row operand, so a lane holds, for

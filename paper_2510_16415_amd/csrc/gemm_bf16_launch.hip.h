@@ -29,19 +29,26 @@ inline bool bf16_dtl_ok(const GemmLaunch& g) {
 }
 
 // 0: 128x128 / 4 waves, 1: 256x256 / 4 waves, 2: 256x256 / 8 waves (register staging),
-// 3: 256x256 / 8 waves with direct-to-LDS staging.
-// Tuning knob for experiments: MECEFO_TILE = S | L4 | L8R | L8 forces one configuration.
+// 3: 256x256 / 8 waves, direct-to-LDS, 2 x 64-K stages, 4: same with 4 x 32-K stages.
+// Tuning knob for experiments: MECEFO_TILE = S | L4 | L8R | L8A | L8B forces one configuration.
 inline int bf16_tile_choice(const GemmLaunch& g) {
   static const char* env = getenv("MECEFO_TILE");
   int c = bf16_use_large(g) ? 3 : 0;
   if (env && env[0] == 'S') c = 0;
-  if (env && env[0] == 'L') c = env[1] == '4' ? 1 : (env[2] == 'R' ? 2 : 3);
-  if (c == 3 && !bf16_dtl_ok(g)) c = 2;
+  if (env && env[0] == 'L') c = env[1] == '4' ? 1 : (env[2] == 'R' ? 2 : (env[2] == 'B' ? 4 : 3));
+  if (c >= 3 && !bf16_dtl_ok(g)) c = 2;
   return c;
 }
 
-template <class Cfg, bool AKC, bool BKC, int EPI, bool DTL = false>
+using PipeA = DtlPipe<64, 2>;   // two 64 KiB stages: refill one stage ahead
+using PipeB = DtlPipe<32, 4>;   // four 32 KiB stages: refill three (half-size) stages ahead
+
+struct NoPipe { static constexpr int LDS_BYTES = 0; };
+
+template <class Cfg, bool AKC, bool BKC, int EPI, class Pipe = NoPipe>
 hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
+  constexpr bool DTL = Pipe::LDS_BYTES > 0;
+  constexpr int LDS = DTL ? Pipe::LDS_BYTES : Cfg::LDS_BYTES;
   constexpr bool DUAL = epi_is_dual(EPI);
   KArgs a;
   a.nprob = g.nprob;
@@ -65,16 +72,15 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
   a.partial = g.partial;
   if (tiles == 0) return hipSuccess;
   void (*kern)(const KArgs);
-  if constexpr (DTL) kern = gemm_bf16_dtl_kernel<Cfg, AKC, BKC, EPI>;
+  if constexpr (DTL) kern = gemm_bf16_dtl_kernel<Cfg, Pipe, AKC, BKC, EPI>;
   else kern = gemm_bf16_kernel<Cfg, AKC, BKC, EPI>;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       Cfg::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(tiles * a.splits), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+  hipLaunchKernelGGL(kern, dim3(tiles * a.splits), dim3(Cfg::NT), LDS, stream, a);
   return hipGetLastError();
 }
 
@@ -83,7 +89,8 @@ hipError_t run_bf16_auto(GemmLaunch& g, hipStream_t stream) {
   switch (bf16_tile_choice(g)) {
     case 1: return run_bf16<CfgL4, AKC, BKC, EPI>(g, stream);
     case 2: return run_bf16<CfgL8, AKC, BKC, EPI>(g, stream);
-    case 3: return run_bf16<CfgL8, AKC, BKC, EPI, true>(g, stream);
+    case 3: return run_bf16<CfgL8, AKC, BKC, EPI, PipeA>(g, stream);
+    case 4: return run_bf16<CfgL8, AKC, BKC, EPI, PipeB>(g, stream);
     default: return run_bf16<CfgS, AKC, BKC, EPI>(g, stream);
   }
 }

@@ -161,12 +161,85 @@ constexpr bool epi_is_dual(int epi) { return epi == EPI_SWIGLU_FWD || epi == EPI
 // 16-byte stores of fp32 when the group lies inside the matrix, else element by element.
 // Row strides are multiples of 8 elements and col0 of 4, so the vector accesses are aligned.
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 __device__ inline bf16x4_t pack_bf16x4(float a, float b, float c, float d) {
   bf16x4_t o;
   o[0] = (__bf16)a; o[1] = (__bf16)b; o[2] = (__bf16)c; o[3] = (__bf16)d;
   return o;
+}
+
+// Eight consecutive output columns of one row (bf16 outputs, 16-byte accesses), used by the
+// LDS-staged epilogue; falls back to single elements at the ragged right edge.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8s_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ inline bf16x8s_t pack_bf16x8(const float (&v)[8]) {
+  bf16x8s_t o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
+  return o;
+}
+
+template <int EPI>
+__device__ inline void epilogue_vec8(const GemmProblem& p, const KArgs& a, int prob, int split, int row,
+                                     int col0, const float (&v)[8], const float (&v2)[8]) {
+  if (row >= p.M) return;
+  if (col0 + 8 > p.N) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) epilogue_elem<EPI, __bf16>(p, a, prob, split, row, col0 + e, v[e], v2[e]);
+    return;
+  }
+  const int64_t idx = (int64_t)row * p.ldc + col0;
+  if constexpr (EPI == EPI_STORE) {
+    *(bf16x8s_t*)((__bf16*)p.C[0] + idx) = pack_bf16x8(v);
+  } else if constexpr (EPI == EPI_SPLIT_F32) {
+    float* base = a.partial + a.partial_off[prob] + (int64_t)split * p.M * p.ldc + idx;
+    const f32x4_t o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
+    *(f32x4_t*)base = o0;
+    *(f32x4_t*)(base + 4) = o1;
+  } else if constexpr (EPI == EPI_GRAD) {
+    if (a.out_f32) {
+      float* c = (float*)p.C[0] + idx;
+      f32x4_t o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
+      if (a.accumulate) { o0 += *(const f32x4_t*)c; o1 += *(const f32x4_t*)(c + 4); }
+      *(f32x4_t*)c = o0;
+      *(f32x4_t*)(c + 4) = o1;
+    } else {
+      bf16x8s_t* c = (bf16x8s_t*)((__bf16*)p.C[0] + idx);
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = v[e];
+      if (a.accumulate) {
+        const bf16x8s_t old = *c;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] += (float)old[e];
+      }
+      *c = pack_bf16x8(o);
+    }
+  } else if constexpr (EPI == EPI_SWIGLU_FWD) {
+    float av[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) av[e] = v[e] * sigmoid_f<false>(v[e]) * v2[e];
+    if (p.C[0]) *(bf16x8s_t*)((__bf16*)p.C[0] + idx) = pack_bf16x8(v);
+    if (p.C[1]) *(bf16x8s_t*)((__bf16*)p.C[1] + idx) = pack_bf16x8(v2);
+    *(bf16x8s_t*)((__bf16*)p.C[2] + idx) = pack_bf16x8(av);
+  } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+    bf16x8s_t* dg = (bf16x8s_t*)((__bf16*)p.C[0] + idx);
+    const bf16x8s_t da8 = *dg;
+    float oa[8], oz[8], og[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float da = (float)da8[e];
+      const float sg = sigmoid_f<false>(v[e]);
+      const float s = v[e] * sg;
+      oa[e] = s * v2[e];
+      oz[e] = da * s;
+      og[e] = da * v2[e] * (sg * (1.0f + v[e] * (1.0f - sg)));
+    }
+    *(bf16x8s_t*)((__bf16*)p.C[2] + idx) = pack_bf16x8(oa);
+    *(bf16x8s_t*)((__bf16*)p.C[1] + idx) = pack_bf16x8(oz);
+    *dg = pack_bf16x8(og);
+  }
 }
 
 template <int EPI>
