@@ -115,13 +115,23 @@ __global__ __launch_bounds__(256) void dgamma_partial_kernel(const T* __restrict
   for (int e = 0; e < VEC; ++e) partial[(int64_t)blockIdx.y * d + cv * VEC + e] = acc[e];
 }
 
+// dgamma[c] = sum over chunks of partial[chunk][c].  A block owns 32 columns; its 8 groups of 32
+// threads each sum a strided eighth of the chunks (coalesced 128-byte rows), then combine in LDS
+// in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restrict__ partial, int nblk, int d,
                                                             void* dgamma, int out_f32, int accumulate) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= d) return;
+  __shared__ float red[8][32];
+  const int cl = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
   float s = 0.f;
-  for (int k = 0; k < nblk; ++k) s += partial[(int64_t)k * d + c];
+  if (c < d)
+    for (int k = g; k < nblk; k += 8) s += partial[(int64_t)k * d + c];
+  red[g][cl] = s;
+  __syncthreads();
+  if (g != 0 || c >= d) return;
+#pragma unroll
+  for (int k = 1; k < 8; ++k) s += red[k][cl];
   if (out_f32) {
     float* o = (float*)dgamma;
     o[c] = accumulate ? o[c] + s : s;
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ G
 }
 
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
-constexpr int kDgammaRows = 64;
+constexpr int kDgammaRows = 32;
 
 }  // namespace
 
@@ -257,10 +267,10 @@ hipError_t launch_rmsnorm_bwd(bool bf16, const void* dU, int64_t lddu, const voi
 hipError_t launch_dgamma_reduce(const float* dg_partial, int nblk, int d, void* dgamma, bool out_f32,
                                 bool bf16, int accumulate, hipStream_t s) {
   if (bf16)
-    hipLaunchKernelGGL(dgamma_reduce_kernel<__bf16>, dim3(blocks_for(d)), dim3(256), 0, s, dg_partial, nblk, d,
+    hipLaunchKernelGGL(dgamma_reduce_kernel<__bf16>, dim3((d + 31) / 32), dim3(256), 0, s, dg_partial, nblk, d,
                        dgamma, (int)out_f32, accumulate);
   else
-    hipLaunchKernelGGL(dgamma_reduce_kernel<float>, dim3(blocks_for(d)), dim3(256), 0, s, dg_partial, nblk, d,
+    hipLaunchKernelGGL(dgamma_reduce_kernel<float>, dim3((d + 31) / 32), dim3(256), 0, s, dg_partial, nblk, d,
                        dgamma, 1, accumulate);
   return hipGetLastError();
 }
