@@ -29,19 +29,21 @@ inline bool bf16_dtl_ok(const GemmLaunch& g) {
 }
 
 // 0: 128x128 / 4 waves, 1: 256x256 / 4 waves, 2: 256x256 / 8 waves (register staging),
-// 3: 256x256 / 8 waves, direct-to-LDS, 2 x 64-K stages, 4: same with 4 x 32-K stages.
-// Tuning knob for experiments: MECEFO_TILE = S | L4 | L8R | L8A | L8B forces one configuration.
+// 3: 256x256 / 8 waves, direct-to-LDS, 2 x 64-K stages.
+// Tuning knob for experiments: MECEFO_TILE = S | L4 | L8R | L8 forces one configuration.
 inline int bf16_tile_choice(const GemmLaunch& g) {
   static const char* env = getenv("MECEFO_TILE");
   int c = bf16_use_large(g) ? 3 : 0;
   if (env && env[0] == 'S') c = 0;
-  if (env && env[0] == 'L') c = env[1] == '4' ? 1 : (env[2] == 'R' ? 2 : (env[2] == 'B' ? 4 : 3));
+  if (env && env[0] == 'L') c = env[1] == '4' ? 1 : (env[2] == 'R' ? 2 : 3);
   if (c >= 3 && !bf16_dtl_ok(g)) c = 2;
   return c;
 }
 
-using PipeA = DtlPipe<64, 2>;   // two 64 KiB stages: refill one stage ahead
-using PipeB = DtlPipe<32, 4>;   // four 32 KiB stages: refill three (half-size) stages ahead
+// Two 64 KiB stages, refilled one stage ahead.  (Measured alternatives that lost: four 32-K stages
+// -- the 64-byte row pieces double the L2 request count; three A + two B buffers, or a second
+// barrier that lets two fills overlap -- the kernel is bound by L2 bandwidth, not fill latency.)
+using PipeA = DtlPipe<64, 2>;
 
 struct NoPipe { static constexpr int LDS_BYTES = 0; };
 
@@ -90,7 +92,6 @@ hipError_t run_bf16_auto(GemmLaunch& g, hipStream_t stream) {
     case 1: return run_bf16<CfgL4, AKC, BKC, EPI>(g, stream);
     case 2: return run_bf16<CfgL8, AKC, BKC, EPI>(g, stream);
     case 3: return run_bf16<CfgL8, AKC, BKC, EPI, PipeA>(g, stream);
-    case 4: return run_bf16<CfgL8, AKC, BKC, EPI, PipeB>(g, stream);
     default: return run_bf16<CfgS, AKC, BKC, EPI>(g, stream);
   }
 }
