@@ -24,6 +24,18 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure (no sparsity)
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch of the C5 GEMM stages: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (two
+# runs of this script), each divided by what the same counter reads for a plain 1 GiB device copy
+# (0.500 and 1.000).  Source and commands: profiles/gemm_bf16_C5_hbm_traffic.md.
+C5_TRAFFIC_BYTES = {
+    "dgrad_down": (1217 + 172) * 2**20,
+    "recompute": (2269 + 516) * 2**20,
+    "dgrad_gate_up": (2064 + 64) * 2**20,
+    "project": (750 + 48) * 2**20,
+    "contract": (1420 + 51) * 2**20,
+    "expand": (578 + 517) * 2**20,
+}
+
 
 def stage_flops(b, d, f, r):
     """Algorithmic FLOPs of each GEMM stage (Sec. 3.4: 2bmn per product; Rcomp without the
@@ -158,9 +170,11 @@ def main():
         "tflops_per_layer": round(flops_layer / (ms_per_step * 1e-3) / 1e12, 1),
         "frac_of_bf16_mfma_peak": round(flops_layer / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "algorithmic_flops_per_layer": flops_layer,
-        "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_kernel stage '{dom}'",
+        "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_dtl_kernel, launch '{dom}'",
                      "achieved": round(dom_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": C5_TRAFFIC_BYTES.get(dom) if cfg.name == "C5" else None,
+                     "flops_per_launch": sf[dom], "ms_per_launch": gemm_stages[dom]["ms"]},
         "stages": stage_report,
         "hbm_bound_kernels": hbm,
     }
