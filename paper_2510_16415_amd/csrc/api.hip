@@ -257,6 +257,7 @@ mecefo_status_t recompute_and_dgrad(const Ctx& c, const Bufs& bf, const void* U,
     GemmLaunch g = new_launch(c, true, false, EPI_STORE);
     g.nprob = 1;
     g.p[0] = prob(DG, DZ, c.ldf, Wg, Wu, d.ld_w_fd, dU, nullptr, nullptr, lddu, b, c.dm, c.ff, 2);
+    g.p[0].kpad_ok = 1;   // DG / DZ padding columns were written as zeros; the weight rows are predicated exactly
     HIP_TRY(launch_gemm(g, s));
   }
   return MECEFO_OK;
@@ -290,8 +291,13 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
     GemmLaunch g = new_launch(c, true, false, EPI_STORE);
     g.nprob = 3;
     for (int i = 0; i < 3; ++i)
+    {
       g.p[i] = prob(in ? X[i] : Gy[i], nullptr, in ? ldx[i] : ldgy[i], P[i].P, nullptr, P[i].ld, T[i], nullptr,
                     nullptr, ldt[i], b, P[i].r, in ? n_in[i] : m_out[i], 1);
+      // the K-contiguous operand is one of the library's own zero-padded [b x f] buffers (A, dG, dZ)
+      const void* a_op = in ? X[i] : Gy[i];
+      g.p[i].kpad_ok = (a_op == base + bf.w.AA || a_op == base + bf.w.DG || a_op == base + bf.w.DZ) ? 1 : 0;
+    }
     HIP_TRY(launch_gemm(g, s));
   }
   {  // contract over tokens: C = (Gy or X)^T T   [rows x r], K = b

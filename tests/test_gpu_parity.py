@@ -56,6 +56,30 @@ def test_block_bwd_skip_ragged(shape, dtype):
     assert_close(got, oracle_block(c), TOL[dtype], label=f"{shape} {dtype}: ")
 
 
+@pytest.mark.parametrize("tile", ["S", "L4", "L8R", "L8"])
+@pytest.mark.parametrize("shape", [(300, 264, 333, 40), (513, 512, 1000, 129), (700, 520, 1365, 264)])
+def test_every_tile_configuration_on_ragged_shapes(shape, tile, monkeypatch):
+    """The launcher picks the tile configuration from the problem size; force each one (128x128
+    and 256x256 register-staged tiles, 4 and 8 waves, and the direct-to-LDS kernel) onto shapes
+    that are ragged against every tile edge, with an odd d_ff and ranks that are not multiples of 8."""
+    monkeypatch.setenv("MECEFO_TILE", tile)
+    b, d, f, r = shape
+    c = make_case(300 + b, b, d, f, r, "bf16")
+    lay = Layer(b, d, f, "bf16", c["Wg"], c["Wu"], c["Wd"], c["gamma"], c["Pg"], c["Pu"], c["Pd"], EPS, pad_w=8)
+    got = lay.block_bwd_skip(c["H"], c["dOut"])
+    assert_close(got, oracle_block(c), TOL["bf16"], label=f"{shape} tile {tile}: ")
+    lay_o = Layer(b, d, f, "bf16", c["Wg"], c["Wu"], c["Wd"], None, c["Pg"], c["Pu"], c["Pd"], EPS)
+    U, dY = c["H"], c["dOut"]
+    dU = torch.full((b, lay_o.ld_act_d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.mecefo_ffn_bwd_exact(lay_o.desc, lay_o.act(U), lay_o.act(dY), lay_o.Wg, lay_o.Wu, lay_o.Wd, None, None, dU,
+                           lay_o.dWg, lay_o.dWu, lay_o.dWd, 0, lay_o.ws)
+    torch.cuda.synchronize()
+    got = lay_o.results()
+    got["dU"] = host(dU, d)
+    assert_close(got, O.ffn_bwd_exact(U, dY, c["Wg"], c["Wu"], c["Wd"]), TOL["bf16"],
+                 keys=["dU", "dWg", "dWu", "dWd"], label=f"exact {shape} tile {tile}: ")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_block_bwd_skip_padded_strides_and_mixed_ranks(dtype):
     """Row strides larger than the widths (padding poisoned with NaN) and a different rank per matrix."""
@@ -208,6 +232,36 @@ def test_skip_leaves_canaries_untouched():
     before = canary.clone()
     lay.block_bwd_skip(c["H"], c["dOut"])
     assert torch.equal(canary, before)
+
+
+def test_hip_graph_capture_and_replay():
+    """The calls allocate nothing and never synchronise, so a layer's backward can be captured
+    into a HIP graph (what a launch-bound small-layer stack wants).  Replays with fresh inputs,
+    separated by eager work and synchronisations, must reproduce the eager results bit for bit."""
+    b, d, f, r = 512, 128, 344, 32
+    cases = [make_case(40 + i, b, d, f, r, "bf16") for i in range(3)]
+    c0 = cases[0]
+    lay = Layer(b, d, f, "bf16", c0["Wg"], c0["Wu"], c0["Wd"], c0["gamma"], c0["Pg"], c0["Pu"], c0["Pd"], EPS)
+    eager = [lay.block_bwd_skip(c["H"], c["dOut"]) for c in cases]      # also warms every kernel up
+    Hd, dOd = lay.act(c0["H"]), lay.act(c0["dOut"])
+    dX = torch.empty_like(dOd)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        B.mecefo_block_bwd_skip(lay.desc, Hd, dOd, lay.gamma, lay.Wg, lay.Wu, lay.Wd, *lay.projs(), lay.side,
+                                dX, lay.dgamma, lay.dWg, lay.dWu, lay.dWd, 0, lay.ws)
+    for i in (1, 2, 0, 2):
+        Hd.copy_(lay.act(cases[i]["H"]))
+        dOd.copy_(lay.act(cases[i]["dOut"]))
+        lay.dWg.fill_(float("nan"))
+        dX.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = lay.results(dX)
+        for k in got:
+            assert np.array_equal(got[k], eager[i][k]), f"replay of case {i}: {k} differs from the eager result"
 
 
 # ----------------------------------------------------------------- the five benchmark configs
