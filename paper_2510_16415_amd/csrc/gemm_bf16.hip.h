@@ -198,7 +198,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
 
   const int nblocks = args.total_tiles * args.splits;
   const TileCoord tc = map_tile(args, xcd_remap(blockIdx.x, nblocks));
-  const GemmProblem& p = args.p[tc.prob];
+  const GemmProblem p = product_view<2>(args.p[tc.prob], tc.z);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN_OUT;
 
   // K range of this block, in stages of 64, over nseg segments each padded to a stage.
@@ -207,8 +207,9 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
   const int kt_per_seg = (K + kBK - 1) / kBK;
   const int kt_total = kt_per_seg * nseg;
   const int kt_chunk = __builtin_amdgcn_readfirstlane((kt_total + args.splits - 1) / args.splits);
-  const int kt_begin = tc.split * kt_chunk;
-  const int kt_end = min(kt_total, kt_begin + kt_chunk);
+  int kt_begin = tc.split * kt_chunk;
+  int kt_end = min(kt_total, kt_begin + kt_chunk);
+  causal_clip(p, m0, n0, BM, kBK, kt_begin, kt_end);
 
   typename LoaderSel<BM, NT, AKC, false>::type la;
   typename LoaderSel<BN, NT, BKC, DUAL>::type lb;
@@ -218,6 +219,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
   const __amdgpu_buffer_rsrc_t ra1 = make_rsrc(p.A[1]);
   const __amdgpu_buffer_rsrc_t rb0 = make_rsrc(p.B[0]);
   const __amdgpu_buffer_rsrc_t rb1 = make_rsrc(p.B[1]);
+  const __amdgpu_buffer_rsrc_t ra2 = make_rsrc(p.A[2]);
+  const __amdgpu_buffer_rsrc_t rb2 = make_rsrc(p.B[2]);
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -245,15 +248,15 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
   }
 
   auto issue_loads = [&](int kt) {
-    const int seg = kt >= kt_per_seg ? 1 : 0;
+    const int seg = (kt >= kt_per_seg ? 1 : 0) + (kt >= 2 * kt_per_seg ? 1 : 0);
     const int k0 = (kt - seg * kt_per_seg) * kBK;
     const bool tail = k0 + kBK > K;
     if (DUAL) {
       la.load(ra0, ra0, k0, K, tail);
       lb.load(rb0, rb1, k0, K, tail);
     } else {
-      la.load(seg ? ra1 : ra0, ra0, k0, K, tail);
-      lb.load(seg ? rb1 : rb0, rb0, k0, K, tail);
+      la.load(seg == 0 ? ra0 : (seg == 1 ? ra1 : ra2), ra0, k0, K, tail);
+      lb.load(seg == 0 ? rb0 : (seg == 1 ? rb1 : rb2), rb0, k0, K, tail);
     }
   };
 

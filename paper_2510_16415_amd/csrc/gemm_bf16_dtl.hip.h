@@ -35,6 +35,16 @@ __device__ inline u32x4_t make_rsrc_words(const void* p) {
   return r;
 }
 
+// Wave-uniform choice between the descriptors of up to three K segments.  Only the base words
+// differ; they are selected word by word and pinned to scalar registers (a vector-typed select is
+// otherwise lowered to vector moves, which the fill instruction cannot take).
+__device__ inline u32x4_t select_rsrc(int seg, const u32x4_t& r0, const u32x4_t& r1, const u32x4_t& r2) {
+  u32x4_t r = r0;
+  r[0] = __builtin_amdgcn_readfirstlane(seg == 0 ? r0[0] : (seg == 1 ? r1[0] : r2[0]));
+  r[1] = __builtin_amdgcn_readfirstlane(seg == 0 ? r0[1] : (seg == 1 ? r1[1] : r2[1]));
+  return r;
+}
+
 __device__ inline uint32_t lds_address(const void* p) {
   return (uint32_t)(size_t)(__attribute__((address_space(3))) const uint8_t*)p;
 }
@@ -209,7 +219,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
 
   const int nblocks = args.total_tiles * args.splits;
   const TileCoord tc = map_tile(args, xcd_remap(blockIdx.x, nblocks));
-  const GemmProblem& p = args.p[tc.prob];
+  const GemmProblem p = product_view<2>(args.p[tc.prob], tc.z);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN_OUT;
 
   const int nseg = DUAL ? 1 : p.nseg;
@@ -217,8 +227,9 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
   const int kt_per_seg = (K + BK - 1) / BK;
   const int kt_total = kt_per_seg * nseg;
   const int kt_chunk = __builtin_amdgcn_readfirstlane((kt_total + args.splits - 1) / args.splits);
-  const int kt_begin = tc.split * kt_chunk;
-  const int kt_end = min(kt_total, kt_begin + kt_chunk);
+  int kt_begin = tc.split * kt_chunk;
+  int kt_end = min(kt_total, kt_begin + kt_chunk);
+  causal_clip(p, m0, n0, BM, BK, kt_begin, kt_end);
 
   typename DmaSel<BK, NT, AKC, false>::type da;
   typename DmaSel<BK, NT, BKC, DUAL>::type db;
@@ -228,6 +239,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
   const u32x4_t ra1 = make_rsrc_words(p.A[1]);
   const u32x4_t rb0 = make_rsrc_words(p.B[0]);
   const u32x4_t rb1 = make_rsrc_words(p.B[1]);
+  const u32x4_t ra2 = make_rsrc_words(p.A[2]);
+  const u32x4_t rb2 = make_rsrc_words(p.B[2]);
   const uint32_t smem_addr = lds_address(smem);
 
   int a_rows[TM], b_rows[TN];
@@ -252,15 +265,15 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   auto issue = [&](int kt, uint32_t stage) {
-    const int seg = kt >= kt_per_seg ? 1 : 0;
+    const int seg = (kt >= kt_per_seg ? 1 : 0) + (kt >= 2 * kt_per_seg ? 1 : 0);
     const int k0 = (DBG & 2) ? 0 : (kt - seg * kt_per_seg) * BK;
     const bool tail = k0 + BK > K;
     if (DUAL) {
       da.issue(ra0, ra0, stage, k0, K, tail);
       db.issue(rb0, rb1, stage + A_BYTES, k0, K, tail);
     } else {
-      da.issue(seg ? ra1 : ra0, ra0, stage, k0, K, tail);
-      if (!(DBG & 4)) db.issue(seg ? rb1 : rb0, rb0, stage + A_BYTES, k0, K, tail);
+      da.issue(select_rsrc(seg, ra0, ra1, ra2), ra0, stage, k0, K, tail);
+      if (!(DBG & 4)) db.issue(select_rsrc(seg, rb0, rb1, rb2), rb0, stage + A_BYTES, k0, K, tail);
     }
   };
 

@@ -16,7 +16,8 @@ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 inline int bf16_tiles(const GemmLaunch& g, int bm, int bn) {
   const bool dual = epi_is_dual(g.epi);
   int t = 0;
-  for (int i = 0; i < g.nprob; ++i) t += cdiv(g.p[i].M, bm) * cdiv(g.p[i].N, dual ? bn / 2 : bn);
+  for (int i = 0; i < g.nprob; ++i)
+    t += cdiv(g.p[i].M, bm) * cdiv(g.p[i].N, dual ? bn / 2 : bn) * (g.p[i].batch > 1 ? g.p[i].batch : 1);
   return t;
 }
 inline bool bf16_use_large(const GemmLaunch& g) { return bf16_tiles(g, 256, 256) >= 160; }
@@ -63,8 +64,9 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
     p.tiles_m = cdiv(p.M, Cfg::BM);
     p.tiles_n = cdiv(p.N, DUAL ? Cfg::BN / 2 : Cfg::BN);
     p.tile_begin = tiles;
-    tiles += p.tiles_m * p.tiles_n;
+    tiles += p.tiles_m * p.tiles_n * (p.batch > 1 ? p.batch : 1);
     if (p.nseg < 2) { p.A[1] = p.A[0]; if (!DUAL) p.B[1] = p.B[0]; }
+    if (p.nseg < 3) { p.A[2] = p.A[0]; p.B[2] = p.B[0]; }
   }
   a.total_tiles = tiles;
   fill_schedule(a);

@@ -1,5 +1,6 @@
 // bf16 GEMM instantiations with both operands K-contiguous: FFN recompute (U Wg^T, U Wu^T
-// with SwiGLU epilogues), the down projection, and the expand step C P^T of Eq. (2).
+// with SwiGLU epilogues), the down projection, the expand step C P^T of Eq. (2), and the
+// attention-score products Q K^T and dO V^T of the standard-mode backward.
 #include "gemm_bf16_launch.hip.h"
 namespace mecefo {
 hipError_t launch_gemm_bf16_nt(GemmLaunch& g, hipStream_t s) {
@@ -8,6 +9,8 @@ hipError_t launch_gemm_bf16_nt(GemmLaunch& g, hipStream_t s) {
     case EPI_GRAD: return run_bf16_auto<true, true, EPI_GRAD>(g, s);
     case EPI_SWIGLU_FWD: return run_bf16_auto<true, true, EPI_SWIGLU_FWD>(g, s);
     case EPI_SWIGLU_BWD: return run_bf16_auto<true, true, EPI_SWIGLU_BWD>(g, s);
+    case EPI_ATTN_P: return run_bf16_auto<true, true, EPI_ATTN_P>(g, s);
+    case EPI_ATTN_DS: return run_bf16_auto<true, true, EPI_ATTN_DS>(g, s);
     default: return hipErrorInvalidValue;
   }
 }

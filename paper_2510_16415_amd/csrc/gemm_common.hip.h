@@ -25,7 +25,7 @@ struct KArgs {
 // XCD segment keeps the tail of a grouped launch short when the problems differ in K.
 inline void fill_schedule(KArgs& a) {
   int idx[3] = {0, 1, 2};
-  auto work = [&](int i) { return i < a.nprob ? (int64_t)a.p[i].K * (a.p[i].nseg > 1 ? 2 : 1) : (int64_t)-1; };
+  auto work = [&](int i) { return i < a.nprob ? (int64_t)a.p[i].K * (a.p[i].nseg > 1 ? a.p[i].nseg : 1) : (int64_t)-1; };
   for (int i = 0; i < 3; ++i)
     for (int j = i + 1; j < 3; ++j)
       if (work(idx[j]) > work(idx[i])) { int t = idx[i]; idx[i] = idx[j]; idx[j] = t; }
@@ -34,7 +34,7 @@ inline void fill_schedule(KArgs& a) {
   for (int x = 0; x < 8; ++x)
     for (int s = 0; s < 3; ++s) {
       const int pi = idx[s];
-      const int T = pi < a.nprob ? a.p[pi].tiles_m * a.p[pi].tiles_n : 0;
+      const int T = pi < a.nprob ? a.p[pi].tiles_m * a.p[pi].tiles_n * (a.p[pi].batch > 1 ? a.p[pi].batch : 1) : 0;
       const int b0 = (int)((int64_t)x * T / 8), b1 = (int)((int64_t)(x + 1) * T / 8);
       a.lstart[x][s] = l;
       a.tstart[x][s] = b0;
@@ -51,7 +51,7 @@ __device__ inline int xcd_remap(int bid, int nblocks) {
   return xcd * q + (xcd < rem ? xcd : rem) + local;
 }
 
-struct TileCoord { int prob, tm, tn, split; };
+struct TileCoord { int prob, tm, tn, split, z; };
 
 // Grouped ordering inside one problem: walk GROUP tile-rows together so that concurrently
 // running blocks reuse both A panels (same tile-row) and B panels (same tile-column).
@@ -70,6 +70,12 @@ __device__ inline TileCoord map_tile(const KArgs& a, int bid) {
   tc.prob = pi;
   int t = l - a.lstart[x][sl] + a.tstart[x][sl];
   const int tiles_m = a.p[pi].tiles_m, tiles_n = a.p[pi].tiles_n;
+  tc.z = 0;
+  if (a.p[pi].batch > 1) {   // batched products: all tiles of one product are consecutive
+    const int per = tiles_m * tiles_n;
+    tc.z = __builtin_amdgcn_readfirstlane(t / per);
+    t -= tc.z * per;
+  }
   constexpr int GROUP = 8;
   const int gsize = GROUP * tiles_n;
   const int g = t / gsize;
@@ -83,6 +89,33 @@ __device__ inline TileCoord map_tile(const KArgs& a, int bid) {
   tc.prob = __builtin_amdgcn_readfirstlane(tc.prob);
   tc.split = __builtin_amdgcn_readfirstlane(tc.split);
   return tc;
+}
+
+// The problem as seen by one product of a batch: operand, output and row-vector pointers moved to
+// product z.  ESZ = bytes per operand / output element.
+template <int ESZ>
+__device__ inline GemmProblem product_view(const GemmProblem& p, int z) {
+  GemmProblem q = p;
+  if (p.batch > 1) {
+    const int zo = __builtin_amdgcn_readfirstlane(z / p.batch_inner), zi = z - zo * p.batch_inner;
+    const int64_t ao = ((int64_t)zo * p.a_bo + (int64_t)zi * p.a_bi) * ESZ;
+    const int64_t bo = ((int64_t)zo * p.b_bo + (int64_t)zi * p.b_bi) * ESZ;
+    const int64_t co = ((int64_t)zo * p.c_bo + (int64_t)zi * p.c_bi) * ESZ;
+    q.A[0] = (const char*)p.A[0] + ao;
+    q.B[0] = (const char*)p.B[0] + bo;
+    q.C[0] = (char*)p.C[0] + co;
+    if (p.rowvec) q.rowvec = p.rowvec + (int64_t)z * p.M;
+  }
+  return q;
+}
+
+// Causal attention products only touch part of K (or nothing): clip the stage range [lo, hi).
+__device__ inline void causal_clip(const GemmProblem& p, int m0, int n0, int bm, int bk, int& lo, int& hi) {
+  if (p.causal == CAUSAL_K_FROM_M) lo = max(lo, m0 / bk);
+  else if (p.causal == CAUSAL_K_UPTO_M) hi = min(hi, (m0 + bm + bk - 1) / bk);
+  else if (p.causal == CAUSAL_TILE && n0 > m0 + bm - 1) hi = lo;
+  lo = __builtin_amdgcn_readfirstlane(lo);
+  hi = __builtin_amdgcn_readfirstlane(hi);
 }
 
 template <typename T> __device__ inline float to_f32(T x) { return (float)x; }
@@ -120,6 +153,21 @@ __device__ inline void epilogue_elem(const GemmProblem& p, const KArgs& a, int p
         T* c = (T*)p.C[0];
         c[idx] = from_f32<T>(a.accumulate ? to_f32<T>(c[idx]) + v : v);
       }
+    }
+  } else if constexpr (EPI == EPI_ATTN_P) {
+    if (col < p.N) {
+      constexpr bool PRECISE = sizeof(T) == 4;
+      float pr = 0.f;
+      if (col <= row) {
+        const float x = v * p.scale - p.rowvec[row];
+        pr = PRECISE ? expf(x) : __builtin_amdgcn_exp2f(1.44269504088896341f * x);
+      }
+      ((T*)p.C[0])[(int64_t)row * p.ldc + col] = from_f32<T>(pr);
+    }
+  } else if constexpr (EPI == EPI_ATTN_DS) {
+    if (col < p.N) {
+      T* c = (T*)p.C[0] + (int64_t)row * p.ldc + col;
+      *c = from_f32<T>(to_f32<T>(*c) * (v - p.rowvec[row]) * p.scale);
     }
   } else if constexpr (EPI == EPI_SWIGLU_FWD) {
     const int64_t idx = (int64_t)row * p.ldc + col;
@@ -192,6 +240,21 @@ __device__ inline void epilogue_vec8(const GemmProblem& p, const KArgs& a, int p
   const int64_t idx = (int64_t)row * p.ldc + col0;
   if constexpr (EPI == EPI_STORE) {
     *(bf16x8s_t*)((__bf16*)p.C[0] + idx) = pack_bf16x8(v);
+  } else if constexpr (EPI == EPI_ATTN_P) {
+    const float lse = p.rowvec[row];
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      o[e] = (col0 + e <= row) ? __builtin_amdgcn_exp2f(1.44269504088896341f * (v[e] * p.scale - lse)) : 0.f;
+    *(bf16x8s_t*)((__bf16*)p.C[0] + idx) = pack_bf16x8(o);
+  } else if constexpr (EPI == EPI_ATTN_DS) {
+    bf16x8s_t* c = (bf16x8s_t*)((__bf16*)p.C[0] + idx);
+    const bf16x8s_t pr = *c;
+    const float dsum = p.rowvec[row];
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (float)pr[e] * (v[e] - dsum) * p.scale;
+    *c = pack_bf16x8(o);
   } else if constexpr (EPI == EPI_SPLIT_F32) {
     float* base = a.partial + a.partial_off[prob] + (int64_t)split * p.M * p.ldc + idx;
     const f32x4_t o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};

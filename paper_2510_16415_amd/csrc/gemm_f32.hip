@@ -19,18 +19,19 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const KArgs args, int a_k
   const int tx = t & 15, ty = t >> 4;
   const int nblocks = args.total_tiles * args.splits;
   const TileCoord tc = map_tile(args, xcd_remap(blockIdx.x, nblocks));
-  const GemmProblem& p = args.p[tc.prob];
+  const GemmProblem p = product_view<4>(args.p[tc.prob], tc.z);
   const int m0 = tc.tm * FT, n0 = tc.tn * FT;
   const int nseg = DUAL ? 1 : p.nseg;
   const int kt_per_seg = (p.K + FK - 1) / FK;
   const int kt_total = kt_per_seg * nseg;
   const int kt_chunk = __builtin_amdgcn_readfirstlane((kt_total + args.splits - 1) / args.splits);
-  const int kt_begin = tc.split * kt_chunk;
-  const int kt_end = min(kt_total, kt_begin + kt_chunk);
+  int kt_begin = tc.split * kt_chunk;
+  int kt_end = min(kt_total, kt_begin + kt_chunk);
+  causal_clip(p, m0, n0, FT, FK, kt_begin, kt_end);
 
   float acc[4][4] = {}, acc2[4][4] = {};
   for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const int seg = kt >= kt_per_seg ? 1 : 0;
+    const int seg = (kt >= kt_per_seg ? 1 : 0) + (kt >= 2 * kt_per_seg ? 1 : 0);
     const int k0 = (kt - seg * kt_per_seg) * FK;
     const float* A = (const float*)p.A[DUAL ? 0 : seg];
     // stage A: 64 x 16 elements, 4 per thread
@@ -101,8 +102,9 @@ hipError_t run_f32(GemmLaunch& g, hipStream_t stream) {
     p.tiles_m = (p.M + FT - 1) / FT;
     p.tiles_n = (p.N + FT - 1) / FT;
     p.tile_begin = tiles;
-    tiles += p.tiles_m * p.tiles_n;
+    tiles += p.tiles_m * p.tiles_n * (p.batch > 1 ? p.batch : 1);
     if (p.nseg < 2) { p.A[1] = p.A[0]; if (!epi_is_dual(EPI)) p.B[1] = p.B[0]; }
+    if (p.nseg < 3) { p.A[2] = p.A[0]; p.B[2] = p.B[0]; }
   }
   a.total_tiles = tiles;
   fill_schedule(a);
@@ -124,6 +126,8 @@ hipError_t launch_gemm_f32(GemmLaunch& g, hipStream_t s) {
     case EPI_GRAD: return run_f32<EPI_GRAD>(g, s);
     case EPI_SWIGLU_FWD: return run_f32<EPI_SWIGLU_FWD>(g, s);
     case EPI_SWIGLU_BWD: return run_f32<EPI_SWIGLU_BWD>(g, s);
+    case EPI_ATTN_P: return run_f32<EPI_ATTN_P>(g, s);
+    case EPI_ATTN_DS: return run_f32<EPI_ATTN_DS>(g, s);
     default: return hipErrorInvalidValue;
   }
 }

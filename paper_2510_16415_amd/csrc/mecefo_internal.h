@@ -11,6 +11,15 @@ enum Epilogue : int {
   EPI_GRAD = 2,        // C0[row, col] (+)= acc                       (gradient dtype, optional accumulate)
   EPI_SWIGLU_FWD = 3,  // dual: G=C0, Z=C1, A=C2 = silu(g)*z
   EPI_SWIGLU_BWD = 4,  // dual: dA read from C0; C0=dG, C1=dZ, C2=A
+  EPI_ATTN_P = 5,      // C0[row, col] = col <= row ? exp(scale * acc - rowvec[row]) : 0   (softmax from saved logsumexp)
+  EPI_ATTN_DS = 6,     // C0[row, col] = C0[row, col] * (acc - rowvec[row]) * scale         (softmax backward, in place on P)
+};
+
+enum CausalK : int {
+  CAUSAL_NONE = 0,
+  CAUSAL_K_FROM_M = 1,   // terms with k < first row of the tile are zero: start the K loop there
+  CAUSAL_K_UPTO_M = 2,   // terms with k > last row of the tile are zero: stop the K loop there
+  CAUSAL_TILE = 3,       // output tiles entirely above the diagonal (col > row) need no K loop at all
 };
 
 // One matrix product C[M x N] = sum over K-segments of opA(A_s) * opB(B_s).
@@ -19,16 +28,23 @@ enum Epilogue : int {
 // Dual products (SwiGLU epilogues) use one segment and B[0], B[1] as the gate and up
 // matrices; both products share A and every size.
 struct GemmProblem {
-  const void* A[2];
-  const void* B[2];
+  const void* A[3];
+  const void* B[3];
   void* C[3];
   int64_t lda, ldb, ldc;
   int M, N, K;
-  int nseg;        // 1 or 2 K segments (ignored for dual products)
+  int nseg;        // 1 to 3 K segments (ignored for dual products)
   int pad_cols;    // SwiGLU epilogues: columns [N, pad_cols) of the outputs are set to zero
   int kpad_ok;     // K-contiguous operands: bytes between K and the next multiple of 8 are known to be zero
   int tile_begin;  // filled by the launcher
   int tiles_m, tiles_n;
+  // Batched products (attention: one product per (sequence, head)): `batch` independent products of
+  // identical size; product z = zo * batch_inner + zi reads A + zo*a_bo + zi*a_bi (elements), etc.
+  int batch, batch_inner;
+  int64_t a_bo, a_bi, b_bo, b_bi, c_bo, c_bi;
+  const float* rowvec;   // attention epilogues: fp32 per output row, product z starts at z * M
+  float scale;           // attention epilogues
+  int causal;            // CausalK
 };
 
 struct GemmLaunch {
