@@ -121,6 +121,50 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
     void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
     void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- Standard-mode backward of one block (Alg. 3, first branch: the rank runs its own layer
+ * without approximation).  Block: H = X + MHA(norm(X; g_attn)); Out = H + FFN(norm(H; g_ffn));
+ * MHA = causal multi-head attention with rotary position embedding (pairs (j, j + dh/2) of a
+ * head rotated by position * theta^(-2j/dh)), softmax scale 1/sqrt(dh), no biases (Sec. 2).
+ * This is the comparator that the neighbor-mode call is measured against (Sec. 3.5 overhead,
+ * Table 6): every gradient is exact.  The FFN activations are recomputed from H as in the
+ * neighbor branch; the attention tensors below are the ones a forward pass keeps. */
+typedef struct {
+  int32_t batch, seq;     /* sequences and tokens per sequence; batch * seq == desc->tokens     */
+  int32_t heads;          /* d_model % heads == 0 and dh = d_model / heads even                   */
+  float rope_theta;       /* rotary base (10000 for LLaMA)                                        */
+  int64_t ld_w_dd;        /* row stride of Wq, Wk, Wv, Wo and their gradients [d x d]             */
+} mecefo_attn_desc_t;
+
+/* Inputs: all [b x d] tensors are token-major with row stride ld_act_d; head h owns columns
+ * [h*dh, (h+1)*dh).  Q and K are stored after the rotation.  L [batch*heads*seq] fp32 is the
+ * row-wise log-sum-exp of the scaled, causally masked scores, index (sequence*heads + head)*seq + s. */
+typedef struct {
+  const void *X, *H, *dOut;                 /* block input, FFN-module input, output gradient  */
+  const void *g_attn, *g_ffn;               /* [d] gains of the two RMSNorms                    */
+  const void *Wq, *Wk, *Wv, *Wo;            /* [d x d], y = W x                                  */
+  const void *Wg, *Wu, *Wd;                 /* FFN weights                                       */
+  const void *Q, *K, *V, *O;                /* saved by the forward pass, [b x d]                */
+  const float* L;                           /* saved log-sum-exp                                  */
+} mecefo_block_inputs_t;
+
+/* Outputs: dX [b x d] (activation dtype; may alias dOut); the rest in grad_dtype, overwritten or
+ * accumulated into as `accumulate` says.  All are required. */
+typedef struct {
+  void* dX;
+  void *dg_attn, *dg_ffn;
+  void *dWq, *dWk, *dWv, *dWo;
+  void *dWg, *dWu, *dWd;
+} mecefo_block_grads_t;
+
+/* Workspace of mecefo_block_bwd_full: dominated by the materialised attention probabilities,
+ * batch*heads*seq*seq elements of the activation dtype. */
+mecefo_status_t mecefo_block_full_workspace_bytes(const mecefo_ffn_desc_t* desc,
+    const mecefo_attn_desc_t* attn, size_t* out_bytes);
+
+mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+    const mecefo_block_inputs_t* in, const mecefo_block_grads_t* out, int accumulate,
+    void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Measurement aid (not part of the hot path; the only calls that create HIP objects).
  * After mecefo_profile_enable(n) every kernel stage enqueued by the calls above is bracketed
  * by a pair of HIP events on the call's own stream, for at most n stage launches.
@@ -139,7 +183,17 @@ typedef enum {
   MECEFO_STAGE_EXPAND = 8,         /* Eq. (2): dW = C P^T                                    */
   MECEFO_STAGE_NORM_BWD = 9,       /* dX = dOut + normbwd(dU), dgamma                        */
   MECEFO_STAGE_WGRAD_EXACT = 10,   /* exact dW = Gy^T X (comparator)                         */
-  MECEFO_STAGE_COUNT = 11
+  MECEFO_STAGE_ATTN_OUT_BWD = 11,  /* dWo = dH^T O and dO = dH Wo                             */
+  MECEFO_STAGE_ATTN_ROWDOT = 12,   /* D = rowsum(dO * O)                                     */
+  MECEFO_STAGE_ATTN_PROBS = 13,    /* P = exp(scale Q K^T - L), causal                       */
+  MECEFO_STAGE_ATTN_DV = 14,       /* dV = P^T dO                                            */
+  MECEFO_STAGE_ATTN_DS = 15,       /* dS = P * (dO V^T - D) * scale                          */
+  MECEFO_STAGE_ATTN_DQ = 16,       /* dQ = dS K                                              */
+  MECEFO_STAGE_ATTN_DK = 17,       /* dK = dS^T Q                                            */
+  MECEFO_STAGE_ROPE_BWD = 18,      /* inverse rotation of dQ, dK (and the angle tables)      */
+  MECEFO_STAGE_QKV_WGRAD = 19,     /* dWq, dWk, dWv = (dQ, dK, dV)^T Xn                      */
+  MECEFO_STAGE_QKV_DGRAD = 20,     /* dXn = dQ Wq + dK Wk + dV Wv                            */
+  MECEFO_STAGE_COUNT = 21
 } mecefo_stage_t;
 mecefo_status_t mecefo_profile_enable(int max_stage_launches);
 mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_stage);

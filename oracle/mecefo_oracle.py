@@ -201,12 +201,15 @@ def mha_fwd(X, g_attn, Wq, Wk, Wv, Wo, heads, batch, seq, eps=1e-6, dtype=np.flo
     sc = (Q @ K.transpose(0, 1, 3, 2)) / dtype(np.sqrt(dh))
     mask = np.triu(np.ones((seq, seq), dtype=bool), 1)
     sc = np.where(mask, -np.inf, sc)
-    sc = sc - sc.max(axis=-1, keepdims=True)
+    mx = sc.max(axis=-1, keepdims=True)
+    sc = sc - mx
     Pm = np.exp(sc)
-    Pm /= Pm.sum(axis=-1, keepdims=True)
+    den = Pm.sum(axis=-1, keepdims=True)
+    Pm /= den
+    L = (mx + np.log(den))[..., 0]          # log-sum-exp of the scaled, masked scores [B,h,S]
     O = (Pm @ V).transpose(0, 2, 1, 3).reshape(batch * seq, d)
     M = O @ _f(Wo, dtype).T
-    cache = dict(Xn=Xn, N=N, rstd=rstd, Q=Q, K=K, V=V, Pm=Pm, O=O, cos=cos, sin=sin,
+    cache = dict(Xn=Xn, N=N, rstd=rstd, Q=Q, K=K, V=V, Pm=Pm, O=O, L=L, cos=cos, sin=sin,
                  heads=heads, batch=batch, seq=seq)
     return M, cache
 

@@ -28,6 +28,23 @@ class Proj(C.Structure):
     _fields_ = [("P", C.c_void_p), ("r", C.c_int32), ("ld", C.c_int64)]
 
 
+class AttnDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("heads", C.c_int32),
+                ("rope_theta", C.c_float), ("ld_w_dd", C.c_int64)]
+
+
+_BLOCK_IN = ["X", "H", "dOut", "g_attn", "g_ffn", "Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd", "Q", "K", "V", "O", "L"]
+_BLOCK_OUT = ["dX", "dg_attn", "dg_ffn", "dWq", "dWk", "dWv", "dWo", "dWg", "dWu", "dWd"]
+
+
+class BlockInputs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _BLOCK_IN]
+
+
+class BlockGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _BLOCK_OUT]
+
+
 class MecefoError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"mecefo status {status}: {message}")
@@ -56,12 +73,16 @@ def lib() -> C.CDLL:
                                          [C.c_int, _vp, C.c_size_t, _vp])
     L.mecefo_block_bwd_skip.argtypes = ([D] + [_vp] * 6 + [Proj] * 3 + [C.c_int] + [_vp] * 5 +
                                         [C.c_int, _vp, C.c_size_t, _vp])
+    L.mecefo_block_full_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(C.c_size_t)]
+    L.mecefo_block_bwd_full.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(BlockInputs), C.POINTER(BlockGrads),
+                                        C.c_int, _vp, C.c_size_t, _vp]
     L.mecefo_profile_enable.argtypes = [C.c_int]
     L.mecefo_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
     L.mecefo_profile_enable.restype = C.c_int
     L.mecefo_profile_collect.restype = C.c_int
     for f in ("mecefo_workspace_bytes", "mecefo_ffn_fwd_recompute", "mecefo_ffn_bwd_exact",
-              "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip"):
+              "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip", "mecefo_block_full_workspace_bytes",
+              "mecefo_block_bwd_full"):
         getattr(L, f).restype = C.c_int
     _lib = L
     return L
@@ -133,8 +154,32 @@ def mecefo_block_bwd_skip(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX
                                        _ptr(dWu), _ptr(dWd), int(accumulate), p, n, _stream(stream)))
 
 
+def make_attn_desc(batch, seq, heads, ld_w_dd, rope_theta=10000.0) -> AttnDesc:
+    return AttnDesc(batch, seq, heads, rope_theta, ld_w_dd)
+
+
+def mecefo_block_full_workspace_bytes(desc: FfnDesc, attn: AttnDesc) -> int:
+    out = C.c_size_t(0)
+    _check(lib().mecefo_block_full_workspace_bytes(C.byref(desc), C.byref(attn), C.byref(out)))
+    return out.value
+
+
+def mecefo_block_bwd_full(desc, attn, inputs: dict, grads: dict, accumulate, ws, stream=None):
+    """inputs / grads: tensors by the field names of mecefo_block_inputs_t / mecefo_block_grads_t."""
+    def table(cls, names, d):
+        unknown = set(d) - set(names)
+        if unknown:
+            raise KeyError(f"unknown fields {sorted(unknown)}")
+        return cls(*[None if d.get(n) is None else d[n].data_ptr() for n in names])
+    p, n = _ws(ws)
+    tin, tout = table(BlockInputs, _BLOCK_IN, inputs), table(BlockGrads, _BLOCK_OUT, grads)
+    _check(lib().mecefo_block_bwd_full(C.byref(desc), C.byref(attn), C.byref(tin), C.byref(tout),
+                                       int(accumulate), p, n, _stream(stream)))
+
+
 STAGES = ["norm_fwd", "dgrad_down", "recompute", "swiglu_bwd", "dgrad_gate_up", "project", "contract",
-          "splitk_reduce", "expand", "norm_bwd", "wgrad_exact"]
+          "splitk_reduce", "expand", "norm_bwd", "wgrad_exact", "attn_out_bwd", "attn_rowdot", "attn_probs",
+          "attn_dv", "attn_ds", "attn_dq", "attn_dk", "rope_bwd", "qkv_wgrad", "qkv_dgrad"]
 
 
 def mecefo_profile_enable(max_stage_launches: int):

@@ -342,6 +342,60 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
   return MECEFO_OK;
 }
 
+
+// ---- standard-mode backward (Alg. 3, first branch) ----------------------------------------
+struct FullWs {
+  size_t dH, dQ, dK, dV, D, P, cs, sn, total;
+  int64_t ldp;     // row stride of one [seq x seq] probability matrix
+};
+
+FullWs full_layout(const Ctx& c, const mecefo_attn_desc_t& a, size_t ffn_total) {
+  FullWs w;
+  size_t off = (size_t)up((int64_t)ffn_total, 256);
+  auto take = [&](size_t bytes) { size_t o = off; off += (size_t)up((int64_t)bytes, 256); return o; };
+  const size_t act_d = (size_t)c.b * c.dm * c.esz;
+  w.ldp = up(a.seq, 8);
+  w.dH = take(act_d);
+  w.dQ = take(act_d);
+  w.dK = take(act_d);
+  w.dV = take(act_d);
+  w.D = take((size_t)c.b * a.heads * 4);
+  w.P = take((size_t)a.batch * a.heads * a.seq * w.ldp * c.esz);
+  const int dh = c.dm / (a.heads > 0 ? a.heads : 1);
+  w.cs = take((size_t)a.seq * (dh / 2) * 4);
+  w.sn = take((size_t)a.seq * (dh / 2) * 4);
+  w.total = off + 256;
+  return w;
+}
+
+mecefo_status_t check_attn(const Ctx& c, const mecefo_attn_desc_t* a) {
+  if (!a) return fail(MECEFO_ERR_INVALID_ARG, "attention descriptor is NULL");
+  if (a->batch < 0 || a->seq < 0 || a->heads < 1) return fail(MECEFO_ERR_INVALID_ARG, "batch >= 0, seq >= 0, heads >= 1 required");
+  if ((int64_t)a->batch * a->seq != c.b) return fail(MECEFO_ERR_INVALID_ARG, "batch * seq = %lld differs from tokens = %lld", (long long)a->batch * a->seq, (long long)c.b);
+  if (c.dm % a->heads) return fail(MECEFO_ERR_INVALID_ARG, "d_model %d is not a multiple of heads %d", c.dm, a->heads);
+  const int dh = c.dm / a->heads;
+  if (dh % 2) return fail(MECEFO_ERR_INVALID_ARG, "head dimension %d must be even (rotary pairs)", dh);
+  if (c.bf16 && dh % 8) return fail(MECEFO_ERR_UNSUPPORTED, "bf16 path needs a head dimension that is a multiple of 8 (got %d)", dh);
+  if (c.dm > 16384) return fail(MECEFO_ERR_UNSUPPORTED, "d_model above 16384 is not built for the attention backward");
+  if (a->ld_w_dd < c.dm) return fail(MECEFO_ERR_INVALID_ARG, "ld_w_dd is smaller than d_model");
+  if (c.bf16 && a->ld_w_dd % 8) return fail(MECEFO_ERR_INVALID_ARG, "bf16 path needs ld_w_dd to be a multiple of 8");
+  if (!(a->rope_theta > 0.f)) return fail(MECEFO_ERR_INVALID_ARG, "rope_theta must be positive");
+  if ((int64_t)a->seq * up(a->seq, 8) * c.esz >= kMaxBytes || (int64_t)c.dm * a->ld_w_dd * 4 >= kMaxBytes)
+    return fail(MECEFO_ERR_UNSUPPORTED, "a [seq x seq] score matrix or a [d x d] weight reaches 2 GiB");
+  return MECEFO_OK;
+}
+
+// One batched attention product per (sequence, head): operands are token-major [b x d] tensors
+// (head h at columns h*dh) or the [batch*heads][seq x ldp] probability buffer.
+void per_head_tokens(const mecefo_attn_desc_t& a, int dh, int64_t ld, int64_t* bo, int64_t* bi) {
+  *bo = (int64_t)a.seq * ld;
+  *bi = dh;
+}
+void per_head_scores(const mecefo_attn_desc_t& a, int64_t ldp, int64_t* bo, int64_t* bi) {
+  *bi = (int64_t)a.seq * ldp;
+  *bo = *bi * a.heads;
+}
+
 mecefo_status_t check_lowrank_args(const Ctx& c, const mecefo_proj_t P[3], mecefo_side_t side) {
   if (side != MECEFO_SIDE_INPUT && side != MECEFO_SIDE_OUTPUT) return fail(MECEFO_ERR_INVALID_ARG, "side must be MECEFO_SIDE_INPUT or MECEFO_SIDE_OUTPUT");
   const bool in = side == MECEFO_SIDE_INPUT;
@@ -529,6 +583,201 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
     if (dgamma) HIP_TRY(launch_dgamma_reduce(dgp, c.b > 0 ? nblk : 0, c.dm, dgamma, c.grad_f32, c.bf16, accumulate, s));
   } else if (c.b > 0) {
     HIP_TRY(launch_add(c.bf16, dOut, desc->ld_act_d, dUb, c.dm, dX, desc->ld_act_d, c.b, c.dm, s));
+  }
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_block_full_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+                                                  size_t* out_bytes) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_attn(c, attn));
+  if (!out_bytes) return fail(MECEFO_ERR_INVALID_ARG, "out_bytes is NULL");
+  const int r0[3] = {0, 0, 0};
+  *out_bytes = full_layout(c, *attn, layout(c, r0, MECEFO_SIDE_INPUT, 0).total).total;
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+                                      const mecefo_block_inputs_t* in, const mecefo_block_grads_t* out,
+                                      int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_attn(c, attn));
+  if (!in || !out) return fail(MECEFO_ERR_INVALID_ARG, "input or output table is NULL");
+  const bool any = c.b > 0;
+  TRY(check_ptr(c, in->X, "X", any)); TRY(check_ptr(c, in->H, "H", any)); TRY(check_ptr(c, in->dOut, "dOut", any));
+  TRY(check_ptr(c, in->g_attn, "g_attn")); TRY(check_ptr(c, in->g_ffn, "g_ffn"));
+  TRY(check_ptr(c, in->Wq, "Wq")); TRY(check_ptr(c, in->Wk, "Wk")); TRY(check_ptr(c, in->Wv, "Wv")); TRY(check_ptr(c, in->Wo, "Wo"));
+  TRY(check_ptr(c, in->Wg, "Wg")); TRY(check_ptr(c, in->Wu, "Wu")); TRY(check_ptr(c, in->Wd, "Wd"));
+  TRY(check_ptr(c, in->Q, "Q", any)); TRY(check_ptr(c, in->K, "K", any)); TRY(check_ptr(c, in->V, "V", any)); TRY(check_ptr(c, in->O, "O", any));
+  if (any && !in->L) return fail(MECEFO_ERR_INVALID_ARG, "L is NULL");
+  TRY(check_ptr(c, out->dX, "dX", any));
+  void* grads[9] = {out->dg_attn, out->dg_ffn, out->dWq, out->dWk, out->dWv, out->dWo, out->dWg, out->dWu, out->dWd};
+  for (void* g : grads) {
+    if (!g) return fail(MECEFO_ERR_INVALID_ARG, "every gradient buffer is required");
+    if (c.bf16 && ((uintptr_t)g % 16)) return fail(MECEFO_ERR_INVALID_ARG, "gradient buffers must be 16-byte aligned");
+  }
+  const int r0[3] = {0, 0, 0};
+  const Workspace fw = layout(c, r0, MECEFO_SIDE_INPUT, 0);
+  const FullWs w = full_layout(c, *attn, fw.total);
+  if (w.total > ws_bytes) return fail(MECEFO_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, w.total);
+  if (!ws) return fail(MECEFO_ERR_INVALID_ARG, "workspace is NULL");
+  Bufs bf;
+  bf.base = (char*)up((int64_t)(uintptr_t)ws, 256);
+  bf.w = fw;
+  char* base = bf.base;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const mecefo_ffn_desc_t& d = *desc;
+  const mecefo_attn_desc_t& a = *attn;
+  const int b = (int)c.b, dm = c.dm, dh = dm / a.heads, S = a.seq;
+  const int nblk = rmsnorm_bwd_blocks(c.b);
+  float* rstd = (float*)(base + fw.rstd);
+  float* dgp = (float*)(base + fw.dgp);
+  void* Ub = base + fw.U;       // norm(H), later norm(X)
+  void* dUb = base + fw.dU;     // dU, later dO, later dXn
+  void* dH = base + w.dH;
+  void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
+  float* D = (float*)(base + w.D);
+  void* P = base + w.P;
+  float* cs = (float*)(base + w.cs); float* sn = (float*)(base + w.sn);
+
+  // ---- FFN module, exact: dH = dOut + normbwd(dU), dWg, dWu, dWd, dg_ffn
+  if (any) {
+    STAGE(MECEFO_STAGE_NORM_FWD, s);
+    HIP_TRY(launch_rmsnorm_fwd(c.bf16, in->H, d.ld_act_d, in->g_ffn, d.rms_eps, Ub, dm, rstd, c.b, dm, s));
+  }
+  TRY(recompute_and_dgrad(c, bf, Ub, dm, in->dOut, d.ld_act_d, in->Wg, in->Wu, in->Wd, nullptr, nullptr, dUb, dm, s));
+  {
+    STAGE(MECEFO_STAGE_WGRAD_EXACT, s);
+    GemmLaunch g = new_launch(c, false, false, EPI_GRAD);
+    g.nprob = 3;
+    g.accumulate = accumulate;
+    g.p[0] = prob(base + fw.DG, nullptr, c.ldf, Ub, nullptr, dm, out->dWg, nullptr, nullptr, d.ld_w_fd, c.ff, dm, b, 1);
+    g.p[1] = prob(base + fw.DZ, nullptr, c.ldf, Ub, nullptr, dm, out->dWu, nullptr, nullptr, d.ld_w_fd, c.ff, dm, b, 1);
+    g.p[2] = prob(in->dOut, nullptr, d.ld_act_d, base + fw.AA, nullptr, c.ldf, out->dWd, nullptr, nullptr, d.ld_w_df, dm, c.ff, b, 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  {
+    STAGE(MECEFO_STAGE_NORM_BWD, s);
+    if (any)
+      HIP_TRY(launch_rmsnorm_bwd(c.bf16, dUb, dm, in->H, d.ld_act_d, rstd, in->g_ffn, in->dOut, d.ld_act_d, dH, dm,
+                                 dgp, nblk, c.b, dm, s));
+    HIP_TRY(launch_dgamma_reduce(dgp, any ? nblk : 0, dm, out->dg_ffn, c.grad_f32, c.bf16, accumulate, s));
+  }
+
+  // ---- attention module
+  if (any) {
+    STAGE(MECEFO_STAGE_NORM_FWD, s);
+    HIP_TRY(launch_rmsnorm_fwd(c.bf16, in->X, d.ld_act_d, in->g_attn, d.rms_eps, Ub, dm, rstd, c.b, dm, s));
+  }
+  {  // dWo = dH^T O  [d x d], K = tokens;  dO = dH Wo  [b x d], K = d
+    STAGE(MECEFO_STAGE_ATTN_OUT_BWD, s);
+    GemmLaunch g = new_launch(c, false, false, EPI_GRAD);
+    g.nprob = 1;
+    g.accumulate = accumulate;
+    g.p[0] = prob(dH, nullptr, dm, in->O, nullptr, d.ld_act_d, out->dWo, nullptr, nullptr, a.ld_w_dd, dm, dm, b, 1);
+    HIP_TRY(launch_gemm(g, s));
+    if (any) {
+      GemmLaunch h = new_launch(c, true, false, EPI_STORE);
+      h.nprob = 1;
+      h.p[0] = prob(dH, nullptr, dm, in->Wo, nullptr, a.ld_w_dd, dUb, nullptr, nullptr, dm, b, dm, dm, 1);
+      HIP_TRY(launch_gemm(h, s));
+    }
+  }
+  if (any) {
+    const void* dO = dUb;
+    const float scale = 1.0f / sqrtf((float)dh);
+    int64_t tok_bo, tok_bi, ws_bo, ws_bi, sc_bo, sc_bi;
+    per_head_tokens(a, dh, d.ld_act_d, &tok_bo, &tok_bi);   // caller tensors Q, K, V
+    per_head_tokens(a, dh, dm, &ws_bo, &ws_bi);             // workspace tensors dO, dQ, dK, dV
+    per_head_scores(a, w.ldp, &sc_bo, &sc_bi);
+    auto batched = [&](GemmProblem& p, int64_t abo, int64_t abi, int64_t bbo, int64_t bbi, int64_t cbo, int64_t cbi) {
+      p.batch = a.batch * a.heads;
+      p.batch_inner = a.heads;
+      p.a_bo = abo; p.a_bi = abi; p.b_bo = bbo; p.b_bi = bbi; p.c_bo = cbo; p.c_bi = cbi;
+    };
+    {
+      STAGE(MECEFO_STAGE_ATTN_ROWDOT, s);
+      HIP_TRY(launch_attn_rowdot(c.bf16, dO, dm, in->O, d.ld_act_d, D, c.b, S, a.heads, dh, s));
+    }
+    {  // P = exp(scale Q K^T - L) below the diagonal, 0 above
+      STAGE(MECEFO_STAGE_ATTN_PROBS, s);
+      GemmLaunch g = new_launch(c, true, true, EPI_ATTN_P);
+      g.nprob = 1;
+      g.p[0] = prob(in->Q, nullptr, d.ld_act_d, in->K, nullptr, d.ld_act_d, P, nullptr, nullptr, w.ldp, S, S, dh, 1);
+      batched(g.p[0], tok_bo, tok_bi, tok_bo, tok_bi, sc_bo, sc_bi);
+      g.p[0].rowvec = in->L; g.p[0].scale = scale; g.p[0].causal = CAUSAL_TILE;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {  // dV = P^T dO   [seq x dh], contraction over the query index
+      STAGE(MECEFO_STAGE_ATTN_DV, s);
+      GemmLaunch g = new_launch(c, false, false, EPI_STORE);
+      g.nprob = 1;
+      g.p[0] = prob(P, nullptr, w.ldp, dO, nullptr, dm, dV, nullptr, nullptr, dm, S, dh, S, 1);
+      batched(g.p[0], sc_bo, sc_bi, ws_bo, ws_bi, ws_bo, ws_bi);
+      g.p[0].causal = CAUSAL_K_FROM_M;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {  // dS = P * (dO V^T - D) * scale, in place on P
+      STAGE(MECEFO_STAGE_ATTN_DS, s);
+      GemmLaunch g = new_launch(c, true, true, EPI_ATTN_DS);
+      g.nprob = 1;
+      g.p[0] = prob(dO, nullptr, dm, in->V, nullptr, d.ld_act_d, P, nullptr, nullptr, w.ldp, S, S, dh, 1);
+      batched(g.p[0], ws_bo, ws_bi, tok_bo, tok_bi, sc_bo, sc_bi);
+      g.p[0].rowvec = D; g.p[0].scale = scale; g.p[0].causal = CAUSAL_TILE;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {  // dQ = dS K   [seq x dh], contraction over the key index
+      STAGE(MECEFO_STAGE_ATTN_DQ, s);
+      GemmLaunch g = new_launch(c, true, false, EPI_STORE);
+      g.nprob = 1;
+      g.p[0] = prob(P, nullptr, w.ldp, in->K, nullptr, d.ld_act_d, dQ, nullptr, nullptr, dm, S, dh, S, 1);
+      batched(g.p[0], sc_bo, sc_bi, tok_bo, tok_bi, ws_bo, ws_bi);
+      g.p[0].causal = CAUSAL_K_UPTO_M;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {  // dK = dS^T Q   [seq x dh], contraction over the query index
+      STAGE(MECEFO_STAGE_ATTN_DK, s);
+      GemmLaunch g = new_launch(c, false, false, EPI_STORE);
+      g.nprob = 1;
+      g.p[0] = prob(P, nullptr, w.ldp, in->Q, nullptr, d.ld_act_d, dK, nullptr, nullptr, dm, S, dh, S, 1);
+      batched(g.p[0], sc_bo, sc_bi, tok_bo, tok_bi, ws_bo, ws_bi);
+      g.p[0].causal = CAUSAL_K_FROM_M;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {
+      STAGE(MECEFO_STAGE_ROPE_BWD, s);
+      HIP_TRY(launch_rope_tables(cs, sn, S, dh, (double)a.rope_theta, s));
+      HIP_TRY(launch_rope_bwd(c.bf16, dQ, dm, cs, sn, c.b, S, a.heads, dh, s));
+      HIP_TRY(launch_rope_bwd(c.bf16, dK, dm, cs, sn, c.b, S, a.heads, dh, s));
+    }
+  }
+  {  // dWq, dWk, dWv = (dQ, dK, dV)^T Xn   [d x d], K = tokens
+    STAGE(MECEFO_STAGE_QKV_WGRAD, s);
+    GemmLaunch g = new_launch(c, false, false, EPI_GRAD);
+    g.nprob = 3;
+    g.accumulate = accumulate;
+    void* dst[3] = {out->dWq, out->dWk, out->dWv};
+    const void* src[3] = {dQ, dK, dV};
+    for (int i = 0; i < 3; ++i)
+      g.p[i] = prob(src[i], nullptr, dm, Ub, nullptr, dm, dst[i], nullptr, nullptr, a.ld_w_dd, dm, dm, b, 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  if (any) {  // dXn = dQ Wq + dK Wk + dV Wv   [b x d], three K segments of length d
+    STAGE(MECEFO_STAGE_QKV_DGRAD, s);
+    GemmLaunch g = new_launch(c, true, false, EPI_STORE);
+    g.nprob = 1;
+    g.p[0] = prob(dQ, dK, dm, in->Wq, in->Wk, a.ld_w_dd, dUb, nullptr, nullptr, dm, b, dm, dm, 3);
+    g.p[0].A[2] = dV; g.p[0].B[2] = in->Wv;
+    HIP_TRY(launch_gemm(g, s));
+  }
+  {  // dX = dH + normbwd(dXn), dg_attn
+    STAGE(MECEFO_STAGE_NORM_BWD, s);
+    if (any)
+      HIP_TRY(launch_rmsnorm_bwd(c.bf16, dUb, dm, in->X, d.ld_act_d, rstd, in->g_attn, dH, dm, out->dX, d.ld_act_d,
+                                 dgp, nblk, c.b, dm, s));
+    HIP_TRY(launch_dgamma_reduce(dgp, any ? nblk : 0, dm, out->dg_attn, c.grad_f32, c.bf16, accumulate, s));
   }
   return MECEFO_OK;
 }

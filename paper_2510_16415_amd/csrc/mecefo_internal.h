@@ -86,4 +86,14 @@ hipError_t launch_splitk_reduce(bool bf16, const float* partial, int splits, int
 hipError_t launch_swiglu_bwd(bool bf16, const void* G, const void* Z, int64_t ldgz, void* DG, void* DZ,
                              void* AA, int64_t ldf, int64_t b, int f, int pad_cols, hipStream_t s);
 
+
+// Attention helpers (attention.hip).
+hipError_t launch_rope_tables(float* cs, float* sn, int seq, int dh, double theta, hipStream_t s);
+// In-place inverse rotation of a token-major [tokens x heads*dh] gradient.
+hipError_t launch_rope_bwd(bool bf16, void* X, int64_t ldx, const float* cs, const float* sn, int64_t tokens,
+                           int seq, int heads, int dh, hipStream_t s);
+// D[(sequence*heads + head)*seq + s] = sum over the head's columns of dO * O.
+hipError_t launch_attn_rowdot(bool bf16, const void* dO, int64_t lddo, const void* O, int64_t ldo, float* D,
+                              int64_t tokens, int seq, int heads, int dh, hipStream_t s);
+
 }  // namespace mecefo

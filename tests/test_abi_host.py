@@ -76,3 +76,38 @@ def test_null_and_rank_validation_happens_before_any_launch():
     st = lib.mecefo_block_bwd_skip(C.byref(d), fake, fake, fake, fake, fake, fake, P, P, P, 7,
                                    fake, fake, fake, fake, fake, 0, fake, 1 << 30, None)
     assert st == B.ERR_INVALID_ARG and "side" in B.mecefo_last_error()
+
+
+def test_full_block_descriptor_and_pointer_validation():
+    lib = B.lib()
+    d = B.make_desc(32, 64, 104, B.BF16)
+    ok = B.make_attn_desc(2, 16, 4, 64)
+    n = B.mecefo_block_full_workspace_bytes(d, ok)
+    # at least the probabilities: batch * heads * seq * seq bf16 elements
+    assert n >= 2 * 4 * 16 * 16 * 2
+    big = B.mecefo_block_full_workspace_bytes(B.make_desc(8192, 4096, 11008, B.BF16), B.make_attn_desc(4, 2048, 32, 4096))
+    assert big >= 4 * 32 * 2048 * 2048 * 2
+    for bad, word in [(B.make_attn_desc(2, 15, 4, 64), "tokens"), (B.make_attn_desc(2, 16, 5, 64), "multiple of heads"),
+                      (B.make_attn_desc(2, 16, 32, 64), "multiple of 8"), (B.make_attn_desc(2, 16, 4, 60), "ld_w_dd"),
+                      (B.make_attn_desc(2, 16, 4, 64, rope_theta=0.0), "rope_theta")]:
+        with pytest.raises(B.MecefoError) as e:
+            B.mecefo_block_full_workspace_bytes(d, bad)
+        assert word in str(e.value), (word, str(e.value))
+    with pytest.raises(B.MecefoError) as e:   # odd head dimension
+        B.mecefo_block_full_workspace_bytes(B.make_desc(32, 12, 16, B.F32), B.make_attn_desc(2, 16, 4, 12))
+    assert "even" in str(e.value)
+    fake = 0x10000
+    tin = B.BlockInputs(*([fake] * 17))
+    tout = B.BlockGrads(*([fake] * 10))
+    ws = C.c_void_p(fake)
+    st = lib.mecefo_block_bwd_full(C.byref(d), C.byref(ok), C.byref(tin), C.byref(tout), 0, ws, 16, None)
+    assert st == B.ERR_WORKSPACE_TOO_SMALL
+    tin.L = None
+    st = lib.mecefo_block_bwd_full(C.byref(d), C.byref(ok), C.byref(tin), C.byref(tout), 0, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "L is NULL" in B.mecefo_last_error()
+    tin.L = fake
+    tout.dWo = None
+    st = lib.mecefo_block_bwd_full(C.byref(d), C.byref(ok), C.byref(tin), C.byref(tout), 0, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "gradient buffer" in B.mecefo_last_error()
+    st = lib.mecefo_block_bwd_full(C.byref(d), C.byref(ok), None, C.byref(tout), 0, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG

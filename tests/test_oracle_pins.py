@@ -375,3 +375,34 @@ def test_stack_forward_shapes_and_consistency():
     U, _, _ = O.rmsnorm_fwd(Hs[-1], p["g_ffn"], EPS)
     Y = O.ffn_fwd_recompute(U, p["Wg"], p["Wu"], p["Wd"])[3]
     assert relerr(Hs[-1] + Y, X_last) < 1e-12
+
+
+def test_saved_logsumexp_matches_library_routine_and_softmax():
+    """The log-sum-exp that the forward keeps for the backward: checked against scipy's routine on
+    the scaled, causally masked scores rebuilt from the cached Q and K, and exp(score - L) must
+    give back the probabilities."""
+    from scipy.special import logsumexp
+    p, X, _, heads, batch, seq = tiny(11, b=10, d=8, f=12, heads=2, batch=2, seq=5)
+    _, c = O.mha_fwd(X, p["g_attn"], p["Wq"], p["Wk"], p["Wv"], p["Wo"], heads, batch, seq, EPS)
+    dh = X.shape[1] // heads
+    sc = np.einsum("bhqd,bhkd->bhqk", c["Q"], c["K"]) / np.sqrt(dh)
+    for q in range(seq):
+        ref = logsumexp(sc[:, :, q, : q + 1], axis=-1)
+        assert np.allclose(c["L"][:, :, q], ref, rtol=1e-13, atol=1e-13)
+        assert np.allclose(np.exp(sc[:, :, q, : q + 1] - c["L"][:, :, q, None]), c["Pm"][:, :, q, : q + 1], rtol=1e-12)
+        assert np.all(c["Pm"][:, :, q, q + 1:] == 0)
+
+
+def test_softmax_backward_row_term_equals_output_dot():
+    """sum_k dP[q,k] P[q,k] = <dO[q], O[q]> per head (O = P V, dP = dO V^T): the identity that lets a
+    backward pass work from the saved output instead of the probabilities."""
+    p, X, dOut, heads, batch, seq = tiny(12, b=8, d=8, f=12, heads=2, batch=2, seq=4)
+    _, c = O.mha_fwd(X, p["g_attn"], p["Wq"], p["Wk"], p["Wv"], p["Wo"], heads, batch, seq, EPS)
+    d = X.shape[1]
+    dh = d // heads
+    dO = (dOut @ p["Wo"]).reshape(batch, seq, heads, dh).transpose(0, 2, 1, 3)
+    dPm = dO @ c["V"].transpose(0, 1, 3, 2)
+    lhs = np.sum(dPm * c["Pm"], axis=-1)
+    Oh = c["O"].reshape(batch, seq, heads, dh).transpose(0, 2, 1, 3)
+    rhs = np.sum(dO * Oh, axis=-1)
+    assert np.allclose(lhs, rhs, rtol=1e-12, atol=1e-13)
