@@ -188,11 +188,13 @@ def main():
 
 
 def overhead(B, torch, desc, b, d, f, r, ldf, U, dY, Wg, Wu, Wd, projs, dU, dWg, dWu, dWd, ws, deg_block_ms, cfg):
-    """Normal-vs-degraded step time.  (A) FFN only, all own kernels: Eq. (2) backward vs the exact
-    backward from saved activations (12bdf) vs recompute + exact Wgrad (16bdf).  (B) whole block:
-    the standard MHA backward (about 16 b d^2 + 8 b s d FLOPs) is not built here; its time is
-    estimated at the GEMM rate measured for the exact FFN backward and labelled as an estimate."""
-    G = torch.empty(b, ldf, dtype=torch.bfloat16, device=U.device)
+    """Normal-vs-degraded step time, all with this library's kernels.  (A) FFN only: Eq. (2) backward
+    vs the exact backward from saved activations (12bdf) vs recompute + exact Wgrad (16bdf).
+    (B) whole block: mecefo_block_bwd_full (exact FFN + attention backward from the tensors a forward
+    pass keeps; they are fabricated with torch outside the timed region) vs the degraded block."""
+    dev = U.device
+    bf = torch.bfloat16
+    G = torch.empty(b, ldf, dtype=bf, device=dev)
     Z = torch.empty_like(G)
     A = torch.empty_like(G)
     B.mecefo_ffn_fwd_recompute(desc, U, Wg, Wu, None, G, Z, A, None, ws)
@@ -210,18 +212,59 @@ def overhead(B, torch, desc, b, d, f, r, ldf, U, dY, Wg, Wu, Wd, projs, dU, dWg,
                                                   dWd, 0, ws))
     t_saved = timed(lambda: B.mecefo_ffn_bwd_exact(desc, U, dY, Wg, Wu, Wd, G, Z, dU, dWg, dWu, dWd, 0, ws))
     t_rec = timed(lambda: B.mecefo_ffn_bwd_exact(desc, U, dY, Wg, Wu, Wd, None, None, dU, dWg, dWu, dWd, 0, ws))
-    exact_rate = 12 * b * d * f / (t_saved * 1e-3)
-    mha_flops = 16 * b * d * d + 8 * b * cfg.seq * d
-    mha_ms_est = mha_flops / exact_rate * 1e3
+    del G, Z, A
+
+    # whole block, standard mode
+    heads, S, nb = cfg.heads, cfg.seq, cfg.batch
+    dh = d // heads
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(12345 + cfg.index)
+    rn = lambda rows, cols, std=1.0: (torch.randn(rows, cols, generator=gen, device=dev) * std).to(bf)
+    inp = dict(X=rn(b, d), H=U, dOut=dY, g_attn=torch.ones(d, dtype=bf, device=dev),
+               g_ffn=torch.ones(d, dtype=bf, device=dev), Wg=Wg, Wu=Wu, Wd=Wd,
+               Q=rn(b, d), K=rn(b, d), V=rn(b, d), O=rn(b, d, 0.1))
+    for k in ("Wq", "Wk", "Wv", "Wo"):
+        inp[k] = rn(d, d, 0.02)
+    L = torch.empty(nb, heads, S, dtype=torch.float32, device=dev)
+    mask = torch.triu(torch.ones(S, S, dtype=torch.bool, device=dev), 1)
+    for i in range(nb):      # log-sum-exp of the causal scaled scores of the fabricated Q, K
+        q = inp["Q"][i * S:(i + 1) * S].view(S, heads, dh).transpose(0, 1).float()
+        k = inp["K"][i * S:(i + 1) * S].view(S, heads, dh).transpose(0, 1).float()
+        sc = (q @ k.transpose(1, 2)) / dh ** 0.5
+        L[i] = torch.logsumexp(sc.masked_fill(mask, float("-inf")), dim=-1)
+        del q, k, sc
+    inp["L"] = L.reshape(-1)
+    attn = B.make_attn_desc(nb, S, heads, d)
+    wsf = torch.empty(B.mecefo_block_full_workspace_bytes(desc, attn), dtype=torch.uint8, device=dev)
+    grads = dict(dX=torch.empty(b, d, dtype=bf, device=dev), dg_attn=torch.zeros(d, device=dev),
+                 dg_ffn=torch.zeros(d, device=dev), dWg=dWg, dWu=dWu, dWd=dWd)
+    for k in ("dWq", "dWk", "dWv", "dWo"):
+        grads[k] = torch.zeros(d, d, device=dev)
+    full = lambda: B.mecefo_block_bwd_full(desc, attn, inp, grads, 0, wsf)
+    t_full = timed(full, 10)
+    B.mecefo_profile_enable(32 * 5)
+    for _ in range(5):
+        full()
+    torch.cuda.synchronize()
+    stages = {k: round(ms / 5, 4) for k, (ms, n) in B.mecefo_profile_collect().items()}
+    # attention core FLOPs with the causal half: five [S x S x dh] products per (sequence, head)
+    core_flops = 5 * nb * heads * S * S * dh
+    core_ms = sum(stages.get(k, 0.0) for k in ("attn_probs", "attn_dv", "attn_ds", "attn_dq", "attn_dk"))
+    full_flops = 16 * b * d * f + 16 * b * d * d + core_flops
     return {
         "ffn_degraded_lowrank_ms": round(t_lr, 4),
         "ffn_exact_from_saved_ms": round(t_saved, 4),
         "ffn_recompute_exact_wgrad_ms": round(t_rec, 4),
         "ffn_degraded_over_exact": round(t_lr / t_saved, 4),
         "block_degraded_ms": round(deg_block_ms, 4),
-        "block_full_ms_est": round(t_saved + mha_ms_est, 4),
-        "block_degraded_over_full_est": round(deg_block_ms / (t_saved + mha_ms_est), 4),
-        "note": "MHA backward not built: estimated from its FLOPs at the measured exact-FFN GEMM rate",
+        "block_full_ms": round(t_full, 4),
+        "block_degraded_over_full": round(deg_block_ms / t_full, 4),
+        "block_full_tflops": round(full_flops / (t_full * 1e-3) / 1e12, 1),
+        "attention_core_ms": round(core_ms, 4),
+        "attention_core_tflops": round(core_flops / (core_ms * 1e-3) / 1e12, 1) if core_ms > 0 else None,
+        "block_full_stages_ms": stages,
+        "note": "block_full: FFN recomputed from H with exact weight gradients + attention backward from "
+                "saved Q, K, V, O, L (fabricated outside the timed region); all kernels are this library's",
     }
 
 

@@ -221,6 +221,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
   const TileCoord tc = map_tile(args, xcd_remap(blockIdx.x, nblocks));
   const GemmProblem p = product_view<2>(args.p[tc.prob], tc.z);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN_OUT;
+  if (causal_tile_unused(p, m0, n0, BM)) return;
 
   const int nseg = DUAL ? 1 : p.nseg;
   const int K = p.K;

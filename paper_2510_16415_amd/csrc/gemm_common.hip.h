@@ -109,6 +109,15 @@ __device__ inline GemmProblem product_view(const GemmProblem& p, int z) {
   return q;
 }
 
+// Softmax products (CAUSAL_TILE): output blocks of 256 x 256 that lie entirely above the diagonal
+// are never read by the products that consume the probabilities (their K loops are clipped to the
+// same 256-aligned blocks whatever tile size they run with), so tiles inside such a block are
+// neither computed nor written.  Tiles above the diagonal but inside a diagonal block still write
+// their zeros.  Uniform over the workgroup.
+__device__ inline bool causal_tile_unused(const GemmProblem& p, int m0, int n0, int bm) {
+  return p.causal == CAUSAL_TILE && (n0 >> 8) > ((m0 + bm - 1) >> 8);
+}
+
 // Causal attention products only touch part of K (or nothing): clip the stage range [lo, hi).
 __device__ inline void causal_clip(const GemmProblem& p, int m0, int n0, int bm, int bk, int& lo, int& hi) {
   if (p.causal == CAUSAL_K_FROM_M) lo = max(lo, m0 / bk);

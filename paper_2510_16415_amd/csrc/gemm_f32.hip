@@ -21,6 +21,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const KArgs args, int a_k
   const TileCoord tc = map_tile(args, xcd_remap(blockIdx.x, nblocks));
   const GemmProblem p = product_view<4>(args.p[tc.prob], tc.z);
   const int m0 = tc.tm * FT, n0 = tc.tn * FT;
+  if (causal_tile_unused(p, m0, n0, FT)) return;
   const int nseg = DUAL ? 1 : p.nseg;
   const int kt_per_seg = (p.K + FK - 1) / FK;
   const int kt_total = kt_per_seg * nseg;

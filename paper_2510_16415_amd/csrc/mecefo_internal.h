@@ -19,7 +19,7 @@ enum CausalK : int {
   CAUSAL_NONE = 0,
   CAUSAL_K_FROM_M = 1,   // terms with k < first row of the tile are zero: start the K loop there
   CAUSAL_K_UPTO_M = 2,   // terms with k > last row of the tile are zero: stop the K loop there
-  CAUSAL_TILE = 3,       // output tiles entirely above the diagonal (col > row) need no K loop at all
+  CAUSAL_TILE = 3,       // output tiles entirely above the diagonal need no K loop; whole 256-blocks above it are not written
 };
 
 // One matrix product C[M x N] = sum over K-segments of opA(A_s) * opB(B_s).
