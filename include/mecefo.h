@@ -165,6 +165,26 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
     const mecefo_block_inputs_t* in, const mecefo_block_grads_t* out, int accumulate,
     void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- Projection refresh (Alg. 3: every tau neighbor steps the projection of a layer is recomputed
+ * from its current weights, W = U S V^T, V1 = the first r columns of V; Sec. 3.4).
+ * The call approximates span(V1) on the GEMM core without an SVD or a QR factorisation:
+ * `power_iters` rounds of subspace iteration X <- W^T (W X), each followed by a Frobenius
+ * normalisation and `cond_steps` quintic Newton-Schulz steps X <- X (aI + bA + cA^2), A = X^T X,
+ * which re-condition the basis without changing its span; `polish_steps` cubic steps
+ * X <- X + X (I - X^T X)/2 then drive X^T X to the identity.  The error of the subspace after q
+ * rounds is of order (s_{r+1}/s_r)^(2q) times the error of the start basis (plus the rounding of
+ * the storage type), so a warm start (the previous projection) needs few rounds.
+ * In: W [m x n] row-major (row stride ldw); left = 0: right singular vectors (the paper's V1,
+ * basis [n x r]); left = 1: left singular vectors (basis [m x r], for MECEFO_SIDE_OUTPUT);
+ * V0 [dim x r] (row stride ldv) start basis of full column rank: the previous projection or
+ * Gaussian noise.  Out: P [dim x r] (row stride ldp), the same layout mecefo_proj_t takes; P may
+ * alias V0.  1 <= r <= min(m, n).  bf16: 16-byte aligned pointers, ldw % 8 == 0.  Only enqueues. */
+mecefo_status_t mecefo_projection_workspace_bytes(mecefo_dtype_t dtype, int m, int n, int r, int left,
+    size_t* out_bytes);
+mecefo_status_t mecefo_projection_refresh(mecefo_dtype_t dtype, const void* W, int m, int n, int64_t ldw,
+    int left, const void* V0, int64_t ldv, int r, int power_iters, int cond_steps, int polish_steps,
+    void* P, int64_t ldp, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Measurement aid (not part of the hot path; the only calls that create HIP objects).
  * After mecefo_profile_enable(n) every kernel stage enqueued by the calls above is bracketed
  * by a pair of HIP events on the call's own stream, for at most n stage launches.

@@ -76,13 +76,16 @@ def lib() -> C.CDLL:
     L.mecefo_block_full_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(C.c_size_t)]
     L.mecefo_block_bwd_full.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(BlockInputs), C.POINTER(BlockGrads),
                                         C.c_int, _vp, C.c_size_t, _vp]
+    L.mecefo_projection_workspace_bytes.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_size_t)]
+    L.mecefo_projection_refresh.argtypes = [C.c_int, _vp, C.c_int, C.c_int, C.c_int64, C.c_int, _vp, C.c_int64,
+                                            C.c_int, C.c_int, C.c_int, C.c_int, _vp, C.c_int64, _vp, C.c_size_t, _vp]
     L.mecefo_profile_enable.argtypes = [C.c_int]
     L.mecefo_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
     L.mecefo_profile_enable.restype = C.c_int
     L.mecefo_profile_collect.restype = C.c_int
     for f in ("mecefo_workspace_bytes", "mecefo_ffn_fwd_recompute", "mecefo_ffn_bwd_exact",
               "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip", "mecefo_block_full_workspace_bytes",
-              "mecefo_block_bwd_full"):
+              "mecefo_block_bwd_full", "mecefo_projection_workspace_bytes", "mecefo_projection_refresh"):
         getattr(L, f).restype = C.c_int
     _lib = L
     return L
@@ -175,6 +178,19 @@ def mecefo_block_bwd_full(desc, attn, inputs: dict, grads: dict, accumulate, ws,
     tin, tout = table(BlockInputs, _BLOCK_IN, inputs), table(BlockGrads, _BLOCK_OUT, grads)
     _check(lib().mecefo_block_bwd_full(C.byref(desc), C.byref(attn), C.byref(tin), C.byref(tout),
                                        int(accumulate), p, n, _stream(stream)))
+
+
+def mecefo_projection_workspace_bytes(dtype, m, n, r, left=0) -> int:
+    out = C.c_size_t(0)
+    _check(lib().mecefo_projection_workspace_bytes(dtype, m, n, r, int(left), C.byref(out)))
+    return out.value
+
+
+def mecefo_projection_refresh(dtype, W, m, n, ldw, left, V0, ldv, r, power_iters, cond_steps, polish_steps,
+                              P, ldp, ws, stream=None):
+    p, nb = _ws(ws)
+    _check(lib().mecefo_projection_refresh(dtype, _ptr(W), m, n, ldw, int(left), _ptr(V0), ldv, r, power_iters,
+                                           cond_steps, polish_steps, _ptr(P), ldp, p, nb, _stream(stream)))
 
 
 STAGES = ["norm_fwd", "dgrad_down", "recompute", "swiglu_bwd", "dgrad_gate_up", "project", "contract",

@@ -22,16 +22,22 @@ hipError_t launch_gemm(GemmLaunch& g, hipStream_t s) {
 }
 }  // namespace mecefo
 
-namespace {
-
+namespace mecefo {
 thread_local char g_err[512] = "";
 
-mecefo_status_t fail(mecefo_status_t st, const char* fmt, ...) {
+int fail(int st, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
   va_end(ap);
   return st;
+}
+}  // namespace mecefo
+
+namespace {
+
+template <typename... T> mecefo_status_t fail(mecefo_status_t st, const char* fmt, T... a) {
+  return (mecefo_status_t)mecefo::fail((int)st, fmt, a...);
 }
 
 constexpr int64_t kMaxBytes = (int64_t)1 << 31;

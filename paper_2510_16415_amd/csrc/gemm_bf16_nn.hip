@@ -5,6 +5,7 @@ namespace mecefo {
 hipError_t launch_gemm_bf16_nn(GemmLaunch& g, hipStream_t s) {
   switch (g.epi) {
     case EPI_STORE: return run_bf16_auto<true, false, EPI_STORE>(g, s);
+    case EPI_GRAD: return run_bf16_auto<true, false, EPI_GRAD>(g, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -60,6 +60,9 @@ struct GemmLaunch {
   int64_t partial_off[3];
 };
 
+// Records the thread-local error text returned by mecefo_last_error() and returns `status`.
+int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // Returns hipSuccess or the launch error.  Only enqueues.
 hipError_t launch_gemm(GemmLaunch& g, hipStream_t stream);
 hipError_t launch_gemm_bf16(GemmLaunch& g, hipStream_t stream);

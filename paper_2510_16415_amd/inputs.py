@@ -145,3 +145,21 @@ def pad_cols(x: np.ndarray, ld: int) -> np.ndarray:
     out = np.zeros((x.shape[0], ld), dtype=x.dtype)
     out[:, : x.shape[1]] = x
     return out
+
+
+def planted_spectrum_matrix(rng: np.random.Generator, m: int, n: int, sigma: np.ndarray, dtype: str):
+    """W [m x n] = U diag(sigma) V^T with orthonormal U [m x k], V [n x k] (QR of Gaussians),
+    k = len(sigma) <= min(m, n), sigma in descending order.  Returns (W cast to dtype, U, V) so
+    that tests know the singular subspaces by construction (before the cast's rounding)."""
+    k = len(sigma)
+    U, _ = np.linalg.qr(rng.standard_normal((m, k)))
+    V, _ = np.linalg.qr(rng.standard_normal((n, k)))
+    W = (U * np.asarray(sigma, dtype=np.float64)[None, :]) @ V.T
+    return _cast(W.astype(np.float32), dtype), U, V
+
+
+def spectrum_with_gap(k: int, r: int, decay: float = 0.98, gap: float = 0.5) -> np.ndarray:
+    """Geometric spectrum sigma_i = decay^i with one extra factor `gap` between index r-1 and r."""
+    s = decay ** np.arange(k, dtype=np.float64)
+    s[r:] *= gap
+    return s

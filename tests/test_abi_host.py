@@ -111,3 +111,29 @@ def test_full_block_descriptor_and_pointer_validation():
     assert st == B.ERR_INVALID_ARG and "gradient buffer" in B.mecefo_last_error()
     st = lib.mecefo_block_bwd_full(C.byref(d), C.byref(ok), None, C.byref(tout), 0, ws, 1 << 30, None)
     assert st == B.ERR_INVALID_ARG
+
+
+def test_projection_refresh_validation():
+    lib = B.lib()
+    n = B.mecefo_projection_workspace_bytes(B.BF16, 11008, 4096, 1024)
+    # fp32 master copies of the basis (twice) and of W X dominate
+    assert n >= (2 * 4096 + 11008) * 1024 * 4
+    assert B.mecefo_projection_workspace_bytes(B.BF16, 11008, 4096, 1024, left=1) > n
+    for args, word in [((B.BF16, 64, 32, 33), "rank"), ((B.BF16, 0, 32, 4), "m >= 1"), ((7, 64, 32, 4), "dtype")]:
+        with pytest.raises(B.MecefoError) as e:
+            B.mecefo_projection_workspace_bytes(*args)
+        assert word in str(e.value)
+    fake, ws = C.c_void_p(0x10000), C.c_void_p(0x20000)
+    call = lambda *a: lib.mecefo_projection_refresh(*a)
+    st = call(B.BF16, fake, 64, 32, 36, 0, fake, 8, 8, 1, 1, 1, fake, 8, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "ldw" in B.mecefo_last_error()
+    st = call(B.BF16, fake, 64, 32, 32, 0, fake, 4, 8, 1, 1, 1, fake, 8, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "ldv" in B.mecefo_last_error()
+    st = call(B.BF16, fake, 64, 32, 32, 0, None, 8, 8, 1, 1, 1, fake, 8, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "required" in B.mecefo_last_error()
+    st = call(B.BF16, fake, 64, 32, 32, 0, fake, 8, 8, -1, 1, 1, fake, 8, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "iteration" in B.mecefo_last_error()
+    st = call(B.BF16, fake, 64, 32, 32, 0, fake, 8, 8, 1, 1, 1, fake, 8, ws, 64, None)
+    assert st == B.ERR_WORKSPACE_TOO_SMALL
+    st = call(B.BF16, C.c_void_p(0x10004), 64, 32, 32, 0, fake, 8, 8, 1, 1, 1, fake, 8, ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "aligned" in B.mecefo_last_error()
