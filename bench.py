@@ -182,6 +182,8 @@ def main():
     if not args.no_overhead:
         out["overhead_vs_full_bwd"] = overhead(B, torch, desc, b, d, f, r, ldf, H, dOut, Wg, Wu, Wd, projs, dX,
                                               dWg, dWu, dWd, ws, ms_per_step, cfg)
+    if not args.no_overhead:
+        out["projection_refresh"] = projection_refresh(B, torch, Wg, Wd, Pg, Pd, d, f, ldf, r, ms_per_step)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
@@ -266,6 +268,36 @@ def overhead(B, torch, desc, b, d, f, r, ldf, U, dY, Wg, Wu, Wd, projs, dU, dWg,
         "note": "block_full: FFN recomputed from H with exact weight gradients + attention backward from "
                 "saved Q, K, V, O, L (fabricated outside the timed region); all kernels are this library's",
     }
+
+
+def projection_refresh(B, torch, Wg, Wd, Pg, Pd, d, f, ldf, r, deg_block_ms, tau=100):
+    """Alg. 3's projection refresh (every tau = 100 neighbor steps in the paper's runs) with the
+    library's SVD-free subspace iteration: one gate/up-shaped matrix ([f x d], basis in R^d) and the
+    down projection ([d x f], basis in R^f); cold start = 8 rounds from Gaussian noise, warm start =
+    2 rounds from the previous projection; 8 conditioning steps per round, 3 polishing steps.  Amortised cost per step = (2 gate/up + 1 down) / tau."""
+    dev = Wg.device
+
+    def timed(fn, n=3):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / n
+
+    res = {}
+    for name, W, m, n, ldw, P in (("gate_up", Wg, f, d, d, Pg), ("down", Wd, d, f, ldf, Pd)):
+        ws = torch.empty(B.mecefo_projection_workspace_bytes(B.BF16, m, n, r), dtype=torch.uint8, device=dev)
+        out = torch.empty_like(P)
+        for label, rounds in (("cold_8_rounds", 8), ("warm_2_rounds", 2)):
+            res[f"{name}_{label}_ms"] = round(timed(lambda: B.mecefo_projection_refresh(
+                B.BF16, W, m, n, ldw, 0, P, P.stride(0), r, rounds, 8, 3, out, out.stride(0), ws)), 3)
+        del ws
+    per_step = (2 * res["gate_up_warm_2_rounds_ms"] + res["down_warm_2_rounds_ms"]) / tau
+    res["amortised_ms_per_step_tau100_warm"] = round(per_step, 4)
+    res["amortised_fraction_of_degraded_block"] = round(per_step / deg_block_ms, 4)
+    return res
 
 
 def cpu_baseline(cfg):

@@ -169,9 +169,10 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
  * from its current weights, W = U S V^T, V1 = the first r columns of V; Sec. 3.4).
  * The call approximates span(V1) on the GEMM core without an SVD or a QR factorisation:
  * `power_iters` rounds of subspace iteration X <- W^T (W X), each followed by a Frobenius
- * normalisation and `cond_steps` quintic Newton-Schulz steps X <- X (aI + bA + cA^2), A = X^T X,
+ * normalisation and `cond_steps` quintic Newton-Schulz steps (each multiplies a small singular
+ * value of X by 3.44: about log(k^2)/log(3.44) + 3 steps for k = s_1/s_r; 5 to 8 in practice) X <- X (aI + bA + cA^2), A = X^T X,
  * which re-condition the basis without changing its span; `polish_steps` cubic steps
- * X <- X + X (I - X^T X)/2 then drive X^T X to the identity.  The error of the subspace after q
+ * X <- X + X (I - X^T X)/2 then drive X^T X to the identity (3 reach the bf16 floor, 5 the fp32 one).  The error of the subspace after q
  * rounds is of order (s_{r+1}/s_r)^(2q) times the error of the start basis (plus the rounding of
  * the storage type), so a warm start (the previous projection) needs few rounds.
  * In: W [m x n] row-major (row stride ldw); left = 0: right singular vectors (the paper's V1,

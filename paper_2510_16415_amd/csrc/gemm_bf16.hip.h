@@ -32,6 +32,16 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0x7FFFFFFF, 0x00020000);
 }
 
+// Wave-uniform choice between the base pointers of up to three K segments, pinned to scalar
+// registers half by half (a select on descriptors is otherwise lowered to per-lane moves and
+// every load that uses the result to a loop over lanes).
+__device__ inline const void* select_base(int seg, const void* p0, const void* p1, const void* p2) {
+  const uint64_t a = (uint64_t)(seg == 0 ? p0 : (seg == 1 ? p1 : p2));
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  return (const void*)(((uint64_t)hi << 32) | lo);
+}
+
 // Swizzle: physical 16-byte chunk = logical chunk ^ swz(row).  Distinct for 8 consecutive
 // rows, and rows r, r+8 differ in the low bit, so 16 consecutive rows also spread over
 // 256 bytes of banks.  It depends on row % 16 only, so adding a multiple of 32 rows (the
@@ -217,11 +227,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
   la.init(t, m0, p.M, p.lda);
   lb.init(t, n0, p.N, p.ldb);
   const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(p.A[0]);
-  const __amdgpu_buffer_rsrc_t ra1 = make_rsrc(p.A[1]);
   const __amdgpu_buffer_rsrc_t rb0 = make_rsrc(p.B[0]);
   const __amdgpu_buffer_rsrc_t rb1 = make_rsrc(p.B[1]);
-  const __amdgpu_buffer_rsrc_t ra2 = make_rsrc(p.A[2]);
-  const __amdgpu_buffer_rsrc_t rb2 = make_rsrc(p.B[2]);
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -256,8 +263,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
       la.load(ra0, ra0, k0, K, tail);
       lb.load(rb0, rb1, k0, K, tail);
     } else {
-      la.load(seg == 0 ? ra0 : (seg == 1 ? ra1 : ra2), ra0, k0, K, tail);
-      lb.load(seg == 0 ? rb0 : (seg == 1 ? rb1 : rb2), rb0, k0, K, tail);
+      la.load(make_rsrc(select_base(seg, p.A[0], p.A[1], p.A[2])), ra0, k0, K, tail);
+      lb.load(make_rsrc(select_base(seg, p.B[0], p.B[1], p.B[2])), rb0, k0, K, tail);
     }
   };
 

@@ -34,7 +34,7 @@ inline bool bf16_dtl_ok(const GemmLaunch& g) {
 // Tuning knob for experiments: MECEFO_TILE = S | L4 | L8R | L8 forces one configuration.
 inline int bf16_tile_choice(const GemmLaunch& g) {
   const char* env = getenv("MECEFO_TILE");   // read per launch so that tests can switch it
-  int c = bf16_use_large(g) ? 3 : 0;
+  int c = (bf16_use_large(g) || g.force_large) ? 3 : 0;
   if (env && env[0] == 'S') c = 0;
   if (env && env[0] == 'L') c = env[1] == '4' ? 1 : (env[2] == 'R' ? 2 : 3);
   if (c >= 3 && !bf16_dtl_ok(g)) c = 2;

@@ -6,6 +6,7 @@ hipError_t launch_gemm_bf16_nn(GemmLaunch& g, hipStream_t s) {
   switch (g.epi) {
     case EPI_STORE: return run_bf16_auto<true, false, EPI_STORE>(g, s);
     case EPI_GRAD: return run_bf16_auto<true, false, EPI_GRAD>(g, s);
+    case EPI_SPLIT_F32: return run_bf16_auto<true, false, EPI_SPLIT_F32>(g, s);
     default: return hipErrorInvalidValue;
   }
 }

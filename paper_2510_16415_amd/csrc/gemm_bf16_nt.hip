@@ -7,6 +7,7 @@ hipError_t launch_gemm_bf16_nt(GemmLaunch& g, hipStream_t s) {
   switch (g.epi) {
     case EPI_STORE: return run_bf16_auto<true, true, EPI_STORE>(g, s);
     case EPI_GRAD: return run_bf16_auto<true, true, EPI_GRAD>(g, s);
+    case EPI_SPLIT_F32: return run_bf16_auto<true, true, EPI_SPLIT_F32>(g, s);
     case EPI_SWIGLU_FWD: return run_bf16_auto<true, true, EPI_SWIGLU_FWD>(g, s);
     case EPI_SWIGLU_BWD: return run_bf16_auto<true, true, EPI_SWIGLU_BWD>(g, s);
     case EPI_ATTN_P: return run_bf16_auto<true, true, EPI_ATTN_P>(g, s);

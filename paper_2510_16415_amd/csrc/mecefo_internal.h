@@ -58,6 +58,7 @@ struct GemmLaunch {
   int splits;       // EPI_SPLIT_F32: number of K splits (partials laid out [split][M x ldc] per problem)
   float* partial;   // EPI_SPLIT_F32: base of the partial buffer; problem i starts at partial_off[i]
   int64_t partial_off[3];
+  bool force_large; // bf16: use the 256 x 256 direct-to-LDS configuration even for few tiles (split launches)
 };
 
 // Records the thread-local error text returned by mecefo_last_error() and returns `status`.

@@ -15,6 +15,7 @@ namespace mecefo {
 namespace {
 
 constexpr int kNormBlocks = 256;
+constexpr int kMaxSplits = 8;
 
 // The iterate is kept as an fp32 master copy.  For bf16 weights it enters the MFMA products as the
 // sum of two bf16 matrices (hi = bf16(x), lo = bf16(x - hi): 16 mantissa bits), contracted as two K
@@ -61,12 +62,8 @@ __global__ __launch_bounds__(256) void scale_by_inv_norm_kernel(float* __restric
   }
   __syncthreads();
   const float k = inv;
-  const int64_t n = rows * cols;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int64_t row = i / cols;
-    const int c = (int)(i - row * cols);
-    X[row * ld + c] *= k;
-  }
+  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x)
+    for (int c = threadIdx.x; c < cols; c += 256) X[row * ld + c] *= k;
 }
 
 // out[i, j] = a * (i == j) + b * A[i, j] + c * A2[i, j]   (A2 may be NULL), r x r, fp32 in, T out.
@@ -105,7 +102,7 @@ struct Plan {
   int m, n, r;       // W is [m x n]; the basis has `dim` rows (n for right, m for left vectors)
   int dim, other;
   int64_t ldx;       // row stride of every internal [* x r] buffer
-  size_t X32[2], Y32, Xh, Xl, Yh, Yl, A32, B32, M16, A16, part, total;
+  size_t X32[2], Y32, Xh, Xl, Yh, Yl, A32, B32, M16, A16, part, partial, total;
 };
 
 Plan make_plan(bool bf16, int m, int n, int r, int left) {
@@ -126,6 +123,9 @@ Plan make_plan(bool bf16, int m, int n, int r, int left) {
   p.M16 = take((size_t)r * p.ldx * p.esz);
   p.A16 = take((size_t)r * p.ldx * p.esz);
   p.part = take(kNormBlocks * 4);
+  // split-K partials of the products with few output tiles and a long contraction
+  const int64_t big = (p.dim > p.other ? p.dim : p.other);
+  p.partial = take(bf16 ? (size_t)kMaxSplits * big * p.ldx * 4 : 0);
   p.total = off + 256;
   return p;
 }
@@ -148,6 +148,31 @@ GemmLaunch product(const Plan& pl, bool akc, bool bkc, const void* A_hi, const v
   p.C[0] = C;
   p.lda = lda; p.ldb = ldb; p.ldc = pl.ldx; p.M = M; p.N = N; p.K = K; p.nseg = two ? 2 : 1;
   return g;
+}
+
+// Products with fewer than 160 tiles of 256 x 256 and a long contraction are cut along K so that
+// every CU gets a block; the fp32 partials are then summed in a fixed order.
+hipError_t run_product(const Plan& pl, char* base, GemmLaunch& g, hipStream_t s) {
+  GemmProblem& p = g.p[0];
+  const int tiles = ((p.M + 255) / 256) * ((p.N + 255) / 256);
+  const int stages = ((p.K + 63) / 64) * p.nseg;
+  int splits = 1;
+  if (pl.bf16 && !g.accumulate && tiles < 160 && stages >= 64) {
+    splits = (256 + tiles - 1) / tiles;
+    if (splits > stages / 8) splits = stages / 8;
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    while (splits > 1 && (int64_t)splits * p.M * p.ldc * 4 > (int64_t)kMaxSplits * (pl.dim > pl.other ? pl.dim : pl.other) * pl.ldx * 4) --splits;
+  }
+  if (splits <= 1) return launch_gemm(g, s);
+  float* C = (float*)p.C[0];
+  g.epi = EPI_SPLIT_F32;
+  g.splits = splits;
+  g.partial = (float*)(base + pl.partial);
+  g.partial_off[0] = 0;
+  g.force_large = true;
+  hipError_t e = launch_gemm(g, s);
+  if (e != hipSuccess) return e;
+  return launch_splitk_reduce(false, g.partial, splits, (int64_t)p.M * p.ldc, C, s);
 }
 
 #define HIP_TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return (mecefo_status_t)fail(MECEFO_ERR_LAUNCH, "%s: %s", #x, hipGetErrorString(e__)); } while (0)
@@ -182,7 +207,7 @@ struct Refresh {
   hipError_t normalise() const {  // X /= ||X||_F, so that every singular value is <= 1
     float* part = (float*)(base + pl.part);
     hipLaunchKernelGGL(sumsq_partial_kernel, dim3(kNormBlocks), dim3(256), 0, s, X32(cur), pl.ldx, (int64_t)pl.dim, pl.r, part);
-    hipLaunchKernelGGL(scale_by_inv_norm_kernel, dim3(grid_for((int64_t)pl.dim * pl.r)), dim3(256), 0, s, X32(cur), pl.ldx, (int64_t)pl.dim, pl.r, part, kNormBlocks);
+    hipLaunchKernelGGL(scale_by_inv_norm_kernel, dim3(pl.dim < 4096 ? pl.dim : 4096), dim3(256), 0, s, X32(cur), pl.ldx, (int64_t)pl.dim, pl.r, part, kNormBlocks);
     return hipGetLastError();
   }
 
@@ -198,14 +223,14 @@ struct Refresh {
     const Operand x = opX();
     {  // A = X^T X  [r x r], contraction over the rows of X (hi part only)
       GemmLaunch g = product(pl, false, false, x.hi, nullptr, pl.ldx, x.hi, nullptr, pl.ldx, A32, r, r, dim, 0);
-      HIP_TRY(launch_gemm(g, s));
+      HIP_TRY(run_product(pl, base, g, s));
     }
     const float* A2 = nullptr;
     if (c != 0.f) {  // A^2 = A A^T (A is symmetric)
       HIP_TRY(pl.bf16 ? run_poly<__bf16>(A16, pl.ldx, A32, nullptr, pl.ldx, r, 0.f, 1.f, 0.f, s)
                       : run_poly<float>(A16, pl.ldx, A32, nullptr, pl.ldx, r, 0.f, 1.f, 0.f, s));
       GemmLaunch g = product(pl, true, true, A16, nullptr, pl.ldx, A16, nullptr, pl.ldx, B32, r, r, r, 0);
-      HIP_TRY(launch_gemm(g, s));
+      HIP_TRY(run_product(pl, base, g, s));
       A2 = B32;
     }
     const float da = additive ? a - 1.f : a;
@@ -215,7 +240,7 @@ struct Refresh {
     if (additive) HIP_TRY(hipMemcpyAsync(out, X32(cur), (size_t)dim * pl.ldx * 4, hipMemcpyDeviceToDevice, s));
     // the polynomial of the symmetric A is symmetric: X M = X M^T, so M is the K-contiguous operand
     GemmLaunch g = product(pl, true, true, x.hi, x.lo, pl.ldx, M16, nullptr, pl.ldx, out, dim, r, r, additive ? 1 : 0);
-    HIP_TRY(launch_gemm(g, s));
+    HIP_TRY(run_product(pl, base, g, s));
     cur ^= 1;
     HIP_TRY(split_x());
     return MECEFO_OK;
@@ -241,12 +266,12 @@ struct Refresh {
     // left vectors:  Y = W^T X [n x r] (K = m), X' = W Y [m x r] (K = n)
     GemmLaunch g1 = left ? product(pl, false, false, W, nullptr, ldw, x.hi, x.lo, pl.ldx, Y32(), n, r, m, 0)
                          : product(pl, true, false, W, nullptr, ldw, x.hi, x.lo, pl.ldx, Y32(), m, r, n, 0);
-    HIP_TRY(launch_gemm(g1, s));
+    HIP_TRY(run_product(pl, base, g1, s));
     HIP_TRY(split_y());
     const Operand y = opY();
     GemmLaunch g2 = left ? product(pl, true, false, W, nullptr, ldw, y.hi, y.lo, pl.ldx, X32(cur ^ 1), m, r, n, 0)
                          : product(pl, false, false, W, nullptr, ldw, y.hi, y.lo, pl.ldx, X32(cur ^ 1), n, r, m, 0);
-    HIP_TRY(launch_gemm(g2, s));
+    HIP_TRY(run_product(pl, base, g2, s));
     cur ^= 1;
     return MECEFO_OK;
   }
@@ -310,7 +335,9 @@ mecefo_status_t mecefo_projection_refresh(mecefo_dtype_t dtype, const void* W, i
   if (bf16) hipLaunchKernelGGL((convert2d_kernel<float, __bf16>), dim3(gx), dim3(256), 0, R.s, R.X32(0), ldx, (const __bf16*)V0, ldv, (int64_t)dim, r, (int)ldx);
   else hipLaunchKernelGGL((convert2d_kernel<float, float>), dim3(gx), dim3(256), 0, R.s, R.X32(0), ldx, (const float*)V0, ldv, (int64_t)dim, r, (int)ldx);
   HIP_TRY(hipGetLastError());
-  st = R.condition(cond_steps);
+  // The start basis is only normalised: a previous projection is orthonormal already and Gaussian
+  // noise is well conditioned; without power rounds it is conditioned for the polishing steps.
+  st = R.condition(power_iters == 0 ? cond_steps : 0);
   if (st != MECEFO_OK) return st;
   for (int it = 0; it < power_iters; ++it) {
     st = R.power_round(W, ldw, left);

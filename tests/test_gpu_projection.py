@@ -79,6 +79,19 @@ def test_refresh_bf16_planted_gap(m, n, r, left, pad):
     assert orth_defect(P) < 1e-2
 
 
+def test_light_settings_reach_the_bf16_floor():
+    """Eight conditioning steps per round (s_1/s_r = 13 here: log(13^2)/log(3.44) + 3 = 7.2) and three
+    polishing steps: the settings bench.py times."""
+    rng = np.random.default_rng(8)
+    m, n, r = 1376, 512, 128
+    W, _, _ = I.planted_spectrum_matrix(rng, m, n, I.spectrum_with_gap(n, r), "bf16")
+    want = O.projection_from_svd(W.astype(np.float64), r)
+    P = refresh(W, gaussian_start(8, n, r), r, "bf16", iters=8, cond=8, polish=3)
+    sine, orth = max_principal_sine(P, want), orth_defect(P)
+    print("light settings: sin", sine, "orth", orth)
+    assert sine < 1e-2 and orth < 1e-2
+
+
 def test_warm_start_needs_few_rounds():
     """Alg. 3 refreshes every tau steps from slowly moving weights: starting from the previous
     projection, two rounds recover the new subspace to the accuracy a cold start needs eight for."""
