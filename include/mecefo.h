@@ -165,6 +165,33 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
     const mecefo_block_inputs_t* in, const mecefo_block_grads_t* out, int accumulate,
     void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- Forward of one block in either mode (Alg. 2: the forward pass is the same computation in
+ * both modes; what differs is what is kept for the backward).  Computes
+ *   H = X + MHA(norm(X; g_attn)),  Out = H + FFN(norm(H; g_ffn)).
+ * Standard mode: pass buffers for H, Q, K, V, O [b x d] and L [batch*heads*seq] (fp32); they are
+ * exactly what mecefo_block_bwd_full takes.  Neighbor mode (Sec. 3.3: only the input of the FFN
+ * module is kept): pass H only and NULL for Q, K, V, O, L; the attention tensors then live in the
+ * workspace and are dropped.  Out [b x d] is required and must not alias X; H is required. */
+typedef struct {
+  const void* X;
+  const void *g_attn, *g_ffn;
+  const void *Wq, *Wk, *Wv, *Wo;
+  const void *Wg, *Wu, *Wd;
+} mecefo_block_fwd_inputs_t;
+
+typedef struct {
+  void* Out;
+  void* H;
+  void *Q, *K, *V, *O;   /* all four given, or all four NULL */
+  float* L;              /* given iff Q is given */
+} mecefo_block_fwd_outputs_t;
+
+mecefo_status_t mecefo_block_fwd_workspace_bytes(const mecefo_ffn_desc_t* desc,
+    const mecefo_attn_desc_t* attn, size_t* out_bytes);
+mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+    const mecefo_block_fwd_inputs_t* in, const mecefo_block_fwd_outputs_t* out,
+    void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ---- Projection refresh (Alg. 3: every tau neighbor steps the projection of a layer is recomputed
  * from its current weights, W = U S V^T, V1 = the first r columns of V; Sec. 3.4).
  * The call approximates span(V1) on the GEMM core without an SVD or a QR factorisation:

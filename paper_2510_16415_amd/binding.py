@@ -45,6 +45,18 @@ class BlockGrads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _BLOCK_OUT]
 
 
+_FWD_IN = ["X", "g_attn", "g_ffn", "Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd"]
+_FWD_OUT = ["Out", "H", "Q", "K", "V", "O", "L"]
+
+
+class BlockFwdInputs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _FWD_IN]
+
+
+class BlockFwdOutputs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _FWD_OUT]
+
+
 class MecefoError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"mecefo status {status}: {message}")
@@ -76,6 +88,9 @@ def lib() -> C.CDLL:
     L.mecefo_block_full_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(C.c_size_t)]
     L.mecefo_block_bwd_full.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(BlockInputs), C.POINTER(BlockGrads),
                                         C.c_int, _vp, C.c_size_t, _vp]
+    L.mecefo_block_fwd_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(C.c_size_t)]
+    L.mecefo_block_fwd.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(BlockFwdInputs), C.POINTER(BlockFwdOutputs),
+                                   _vp, C.c_size_t, _vp]
     L.mecefo_projection_workspace_bytes.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_size_t)]
     L.mecefo_projection_refresh.argtypes = [C.c_int, _vp, C.c_int, C.c_int, C.c_int64, C.c_int, _vp, C.c_int64,
                                             C.c_int, C.c_int, C.c_int, C.c_int, _vp, C.c_int64, _vp, C.c_size_t, _vp]
@@ -85,7 +100,8 @@ def lib() -> C.CDLL:
     L.mecefo_profile_collect.restype = C.c_int
     for f in ("mecefo_workspace_bytes", "mecefo_ffn_fwd_recompute", "mecefo_ffn_bwd_exact",
               "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip", "mecefo_block_full_workspace_bytes",
-              "mecefo_block_bwd_full", "mecefo_projection_workspace_bytes", "mecefo_projection_refresh"):
+              "mecefo_block_bwd_full", "mecefo_projection_workspace_bytes", "mecefo_projection_refresh",
+              "mecefo_block_fwd_workspace_bytes", "mecefo_block_fwd"):
         getattr(L, f).restype = C.c_int
     _lib = L
     return L
@@ -178,6 +194,27 @@ def mecefo_block_bwd_full(desc, attn, inputs: dict, grads: dict, accumulate, ws,
     tin, tout = table(BlockInputs, _BLOCK_IN, inputs), table(BlockGrads, _BLOCK_OUT, grads)
     _check(lib().mecefo_block_bwd_full(C.byref(desc), C.byref(attn), C.byref(tin), C.byref(tout),
                                        int(accumulate), p, n, _stream(stream)))
+
+
+def _table(cls, names, d):
+    unknown = set(d) - set(names)
+    if unknown:
+        raise KeyError(f"unknown fields {sorted(unknown)}")
+    return cls(*[None if d.get(n) is None else d[n].data_ptr() for n in names])
+
+
+def mecefo_block_fwd_workspace_bytes(desc: FfnDesc, attn: AttnDesc) -> int:
+    out = C.c_size_t(0)
+    _check(lib().mecefo_block_fwd_workspace_bytes(C.byref(desc), C.byref(attn), C.byref(out)))
+    return out.value
+
+
+def mecefo_block_fwd(desc, attn, inputs: dict, outputs: dict, ws, stream=None):
+    """inputs / outputs: tensors by the field names of mecefo_block_fwd_inputs_t / _outputs_t
+    (omit Q, K, V, O, L for the neighbor-mode forward that keeps only H)."""
+    p, n = _ws(ws)
+    tin, tout = _table(BlockFwdInputs, _FWD_IN, inputs), _table(BlockFwdOutputs, _FWD_OUT, outputs)
+    _check(lib().mecefo_block_fwd(C.byref(desc), C.byref(attn), C.byref(tin), C.byref(tout), p, n, _stream(stream)))
 
 
 def mecefo_projection_workspace_bytes(dtype, m, n, r, left=0) -> int:

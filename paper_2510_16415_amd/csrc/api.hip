@@ -402,6 +402,39 @@ void per_head_scores(const mecefo_attn_desc_t& a, int64_t ldp, int64_t* bo, int6
   *bo = *bi * a.heads;
 }
 
+// ---- block forward ------------------------------------------------------------------------
+struct FwdWs {
+  size_t Xn, rstd, Q, K, V, O, L, A, S32, P, cs, sn, total;
+  int64_t ldp;
+  int hc;        // heads per attention chunk
+};
+
+FwdWs fwd_layout(const Ctx& c, const mecefo_attn_desc_t& a) {
+  FwdWs w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += (size_t)up((int64_t)bytes, 256); return o; };
+  const size_t act_d = (size_t)c.b * c.dm * c.esz;
+  const int dh = c.dm / (a.heads > 0 ? a.heads : 1);
+  w.ldp = up(a.seq, 8);
+  w.Xn = take(act_d);
+  w.rstd = take((size_t)c.b * 4);
+  w.Q = take(act_d); w.K = take(act_d); w.V = take(act_d); w.O = take(act_d);
+  w.L = take((size_t)c.b * a.heads * 4);
+  w.A = take((size_t)c.b * c.ldf * c.esz);
+  // fp32 scores of one chunk of heads of one sequence: at most 256 MiB
+  const int64_t per_head = (int64_t)a.seq * w.ldp * 4;
+  int64_t hc = per_head > 0 ? ((int64_t)256 << 20) / per_head : a.heads;
+  if (hc < 1) hc = 1;
+  if (hc > a.heads) hc = a.heads;
+  w.hc = (int)hc;
+  w.S32 = take((size_t)hc * per_head);
+  w.P = take((size_t)hc * a.seq * w.ldp * c.esz);
+  w.cs = take((size_t)a.seq * (dh / 2) * 4);
+  w.sn = take((size_t)a.seq * (dh / 2) * 4);
+  w.total = off + 256;
+  return w;
+}
+
 mecefo_status_t check_lowrank_args(const Ctx& c, const mecefo_proj_t P[3], mecefo_side_t side) {
   if (side != MECEFO_SIDE_INPUT && side != MECEFO_SIDE_OUTPUT) return fail(MECEFO_ERR_INVALID_ARG, "side must be MECEFO_SIDE_INPUT or MECEFO_SIDE_OUTPUT");
   const bool in = side == MECEFO_SIDE_INPUT;
@@ -755,8 +788,8 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
     {
       STAGE(MECEFO_STAGE_ROPE_BWD, s);
       HIP_TRY(launch_rope_tables(cs, sn, S, dh, (double)a.rope_theta, s));
-      HIP_TRY(launch_rope_bwd(c.bf16, dQ, dm, cs, sn, c.b, S, a.heads, dh, s));
-      HIP_TRY(launch_rope_bwd(c.bf16, dK, dm, cs, sn, c.b, S, a.heads, dh, s));
+      HIP_TRY(launch_rope(c.bf16, dQ, dm, cs, sn, c.b, S, a.heads, dh, true, s));
+      HIP_TRY(launch_rope(c.bf16, dK, dm, cs, sn, c.b, S, a.heads, dh, true, s));
     }
   }
   {  // dWq, dWk, dWv = (dQ, dK, dV)^T Xn   [d x d], K = tokens
@@ -784,6 +817,128 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
       HIP_TRY(launch_rmsnorm_bwd(c.bf16, dUb, dm, in->X, d.ld_act_d, rstd, in->g_attn, dH, dm, out->dX, d.ld_act_d,
                                  dgp, nblk, c.b, dm, s));
     HIP_TRY(launch_dgamma_reduce(dgp, any ? nblk : 0, dm, out->dg_attn, c.grad_f32, c.bf16, accumulate, s));
+  }
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_block_fwd_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+                                                 size_t* out_bytes) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_attn(c, attn));
+  if (!out_bytes) return fail(MECEFO_ERR_INVALID_ARG, "out_bytes is NULL");
+  *out_bytes = fwd_layout(c, *attn).total;
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+                                 const mecefo_block_fwd_inputs_t* in, const mecefo_block_fwd_outputs_t* out,
+                                 void* ws, size_t ws_bytes, void* hip_stream) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_attn(c, attn));
+  if (!in || !out) return fail(MECEFO_ERR_INVALID_ARG, "input or output table is NULL");
+  const bool any = c.b > 0;
+  TRY(check_ptr(c, in->X, "X", any));
+  TRY(check_ptr(c, in->g_attn, "g_attn")); TRY(check_ptr(c, in->g_ffn, "g_ffn"));
+  TRY(check_ptr(c, in->Wq, "Wq")); TRY(check_ptr(c, in->Wk, "Wk")); TRY(check_ptr(c, in->Wv, "Wv")); TRY(check_ptr(c, in->Wo, "Wo"));
+  TRY(check_ptr(c, in->Wg, "Wg")); TRY(check_ptr(c, in->Wu, "Wu")); TRY(check_ptr(c, in->Wd, "Wd"));
+  TRY(check_ptr(c, out->Out, "Out", any)); TRY(check_ptr(c, out->H, "H", any));
+  const int given = (out->Q != nullptr) + (out->K != nullptr) + (out->V != nullptr) + (out->O != nullptr) + (out->L != nullptr);
+  if (given != 0 && given != 5) return fail(MECEFO_ERR_INVALID_ARG, "Q, K, V, O, L must all be given (standard mode) or all be NULL (neighbor mode)");
+  TRY(check_ptr(c, out->Q, "Q", false)); TRY(check_ptr(c, out->K, "K", false)); TRY(check_ptr(c, out->V, "V", false)); TRY(check_ptr(c, out->O, "O", false));
+  if (any && out->Out == in->X) return fail(MECEFO_ERR_INVALID_ARG, "Out must not alias X");
+  const FwdWs w = fwd_layout(c, *attn);
+  if (w.total > ws_bytes) return fail(MECEFO_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, w.total);
+  if (!ws) return fail(MECEFO_ERR_INVALID_ARG, "workspace is NULL");
+  if (!any) return MECEFO_OK;
+  char* base = (char*)up((int64_t)(uintptr_t)ws, 256);
+  hipStream_t s = (hipStream_t)hip_stream;
+  const mecefo_ffn_desc_t& d = *desc;
+  const mecefo_attn_desc_t& a = *attn;
+  const int b = (int)c.b, dm = c.dm, dh = dm / a.heads, S = a.seq;
+  const bool keep = given == 5;
+  void* Xn = base + w.Xn;
+  float* rstd = (float*)(base + w.rstd);
+  void* Q = keep ? out->Q : base + w.Q; void* K = keep ? out->K : base + w.K;
+  void* V = keep ? out->V : base + w.V; void* O = keep ? out->O : base + w.O;
+  float* L = keep ? out->L : (float*)(base + w.L);
+  const int64_t ldq = keep ? d.ld_act_d : dm;   // row stride of Q, K, V, O
+  float* cs = (float*)(base + w.cs); float* sn = (float*)(base + w.sn);
+  float* S32 = (float*)(base + w.S32);
+  void* P = base + w.P;
+  const size_t rowbytes = (size_t)dm * c.esz;
+
+  HIP_TRY(launch_rmsnorm_fwd(c.bf16, in->X, d.ld_act_d, in->g_attn, d.rms_eps, Xn, dm, rstd, c.b, dm, s));
+  {  // Q, K, V = Xn Wq^T, Xn Wk^T, Xn Wv^T  [b x d], K = d
+    GemmLaunch g = new_launch(c, true, true, EPI_STORE);
+    g.nprob = 3;
+    void* dst[3] = {Q, K, V};
+    const void* wt[3] = {in->Wq, in->Wk, in->Wv};
+    for (int i = 0; i < 3; ++i) g.p[i] = prob(Xn, nullptr, dm, wt[i], nullptr, a.ld_w_dd, dst[i], nullptr, nullptr, ldq, b, dm, dm, 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  HIP_TRY(launch_rope_tables(cs, sn, S, dh, (double)a.rope_theta, s));
+  HIP_TRY(launch_rope(c.bf16, Q, ldq, cs, sn, c.b, S, a.heads, dh, false, s));
+  HIP_TRY(launch_rope(c.bf16, K, ldq, cs, sn, c.b, S, a.heads, dh, false, s));
+  const float scale = 1.0f / sqrtf((float)dh);
+  for (int bi = 0; bi < a.batch; ++bi)
+    for (int h0 = 0; h0 < a.heads; h0 += w.hc) {
+      const int hc = a.heads - h0 < w.hc ? a.heads - h0 : w.hc;
+      const int64_t tok = ((int64_t)bi * S * ldq + (int64_t)h0 * dh) * c.esz;
+      const char* Qc = (const char*)Q + tok; const char* Kc = (const char*)K + tok; const char* Vc = (const char*)V + tok;
+      char* Oc = (char*)O + tok;
+      auto batched = [&](GemmProblem& p, int64_t abi, int64_t bbi, int64_t cbi) {
+        p.batch = hc; p.batch_inner = hc;
+        p.a_bo = 0; p.b_bo = 0; p.c_bo = 0; p.a_bi = abi; p.b_bi = bbi; p.c_bi = cbi;
+      };
+      {  // raw scores q.k in fp32, blocks above the diagonal skipped
+        GemmLaunch g = new_launch(c, true, true, EPI_GRAD);
+        g.out_f32 = true;
+        g.nprob = 1;
+        g.p[0] = prob(Qc, nullptr, ldq, Kc, nullptr, ldq, S32, nullptr, nullptr, w.ldp, S, S, dh, 1);
+        // output offsets are counted in operand elements: fp32 scores behind bf16 operands take two each
+        batched(g.p[0], dh, dh, (int64_t)S * w.ldp * (c.bf16 ? 2 : 1));
+        g.p[0].causal = CAUSAL_TILE;
+        HIP_TRY(launch_gemm(g, s));
+      }
+      HIP_TRY(launch_softmax_rows(c.bf16, S32, w.ldp, P, w.ldp, L + ((int64_t)bi * a.heads + h0) * S, hc, S, scale, s));
+      {  // O = P V  [seq x dh], contraction over the keys up to the diagonal block
+        GemmLaunch g = new_launch(c, true, false, EPI_STORE);
+        g.nprob = 1;
+        g.p[0] = prob(P, nullptr, w.ldp, Vc, nullptr, ldq, Oc, nullptr, nullptr, ldq, S, dh, S, 1);
+        batched(g.p[0], (int64_t)S * w.ldp, dh, dh);
+        g.p[0].causal = CAUSAL_K_UPTO_M;
+        HIP_TRY(launch_gemm(g, s));
+      }
+    }
+  // H = X + O Wo^T: the product accumulates onto a copy of X
+  HIP_TRY(hipMemcpy2DAsync(out->H, (size_t)d.ld_act_d * c.esz, in->X, (size_t)d.ld_act_d * c.esz, rowbytes, (size_t)b, hipMemcpyDeviceToDevice, s));
+  {
+    GemmLaunch g = new_launch(c, true, true, EPI_GRAD);
+    g.out_f32 = false;
+    g.accumulate = 1;
+    g.nprob = 1;
+    g.p[0] = prob(O, nullptr, ldq, in->Wo, nullptr, a.ld_w_dd, out->H, nullptr, nullptr, d.ld_act_d, b, dm, dm, 1);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  // FFN: U = norm(H), A = silu(U Wg^T) * (U Wu^T), Out = H + A Wd^T
+  HIP_TRY(launch_rmsnorm_fwd(c.bf16, out->H, d.ld_act_d, in->g_ffn, d.rms_eps, Xn, dm, rstd, c.b, dm, s));
+  void* AA = base + w.A;
+  {
+    GemmLaunch g = new_launch(c, true, true, EPI_SWIGLU_FWD);
+    g.nprob = 1;
+    g.p[0] = prob(Xn, nullptr, dm, in->Wg, in->Wu, d.ld_w_fd, nullptr, nullptr, AA, c.ldf, b, c.ff, dm, 1, (int)c.ldf);
+    HIP_TRY(launch_gemm(g, s));
+  }
+  HIP_TRY(hipMemcpy2DAsync(out->Out, (size_t)d.ld_act_d * c.esz, out->H, (size_t)d.ld_act_d * c.esz, rowbytes, (size_t)b, hipMemcpyDeviceToDevice, s));
+  {
+    GemmLaunch g = new_launch(c, true, true, EPI_GRAD);
+    g.out_f32 = false;
+    g.accumulate = 1;
+    g.nprob = 1;
+    g.p[0] = prob(AA, nullptr, c.ldf, in->Wd, nullptr, d.ld_w_df, out->Out, nullptr, nullptr, d.ld_act_d, b, dm, c.ff, 1);
+    HIP_TRY(launch_gemm(g, s));
   }
   return MECEFO_OK;
 }

@@ -39,7 +39,8 @@ struct GemmProblem {
   int tile_begin;  // filled by the launcher
   int tiles_m, tiles_n;
   // Batched products (attention: one product per (sequence, head)): `batch` independent products of
-  // identical size; product z = zo * batch_inner + zi reads A + zo*a_bo + zi*a_bi (elements), etc.
+  // identical size; product z = zo * batch_inner + zi reads A + zo*a_bo + zi*a_bi, etc.; all six
+  // offsets are counted in operand elements (an fp32 output behind bf16 operands counts two per element).
   int batch, batch_inner;
   int64_t a_bo, a_bi, b_bo, b_bi, c_bo, c_bi;
   const float* rowvec;   // attention epilogues: fp32 per output row, product z starts at z * M
@@ -93,9 +94,12 @@ hipError_t launch_swiglu_bwd(bool bf16, const void* G, const void* Z, int64_t ld
 
 // Attention helpers (attention.hip).
 hipError_t launch_rope_tables(float* cs, float* sn, int seq, int dh, double theta, hipStream_t s);
-// In-place inverse rotation of a token-major [tokens x heads*dh] gradient.
-hipError_t launch_rope_bwd(bool bf16, void* X, int64_t ldx, const float* cs, const float* sn, int64_t tokens,
-                           int seq, int heads, int dh, hipStream_t s);
+// In-place rotary rotation of a token-major [tokens x heads*dh] tensor (inverse: the transpose, for gradients).
+hipError_t launch_rope(bool bf16, void* X, int64_t ldx, const float* cs, const float* sn, int64_t tokens,
+                       int seq, int heads, int dh, bool inverse, hipStream_t s);
+// Causal row softmax of `nprod` fp32 score matrices [seq x lds]: P (storage type) and the log-sum-exp L.
+hipError_t launch_softmax_rows(bool bf16, const float* S, int64_t lds, void* P, int64_t ldp, float* L, int nprod,
+                               int seq, float scale, hipStream_t s);
 // D[(sequence*heads + head)*seq + s] = sum over the head's columns of dO * O.
 hipError_t launch_attn_rowdot(bool bf16, const void* dO, int64_t lddo, const void* O, int64_t ldo, float* D,
                               int64_t tokens, int seq, int heads, int dh, hipStream_t s);

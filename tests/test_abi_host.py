@@ -137,3 +137,26 @@ def test_projection_refresh_validation():
     assert st == B.ERR_WORKSPACE_TOO_SMALL
     st = call(B.BF16, C.c_void_p(0x10004), 64, 32, 32, 0, fake, 8, 8, 1, 1, 1, fake, 8, ws, 1 << 30, None)
     assert st == B.ERR_INVALID_ARG and "aligned" in B.mecefo_last_error()
+
+
+def test_block_fwd_validation():
+    lib = B.lib()
+    d = B.make_desc(32, 64, 104, B.BF16)
+    a = B.make_attn_desc(2, 16, 4, 64)
+    n = B.mecefo_block_fwd_workspace_bytes(d, a)
+    assert n >= 4 * 16 * 16 * 4          # fp32 scores of the heads of one sequence
+    fake = 0x10000
+    tin = B.BlockFwdInputs(*([fake] * 10))
+    tout = B.BlockFwdOutputs(fake + 0x100000, fake, fake, fake, None, fake, fake)
+    ws = C.c_void_p(fake)
+    st = lib.mecefo_block_fwd(C.byref(d), C.byref(a), C.byref(tin), C.byref(tout), ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "all be given" in B.mecefo_last_error()
+    tout = B.BlockFwdOutputs(fake, fake, None, None, None, None, None)
+    st = lib.mecefo_block_fwd(C.byref(d), C.byref(a), C.byref(tin), C.byref(tout), ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "alias" in B.mecefo_last_error()
+    tout = B.BlockFwdOutputs(fake + 0x100000, fake, None, None, None, None, None)
+    st = lib.mecefo_block_fwd(C.byref(d), C.byref(a), C.byref(tin), C.byref(tout), ws, 16, None)
+    assert st == B.ERR_WORKSPACE_TOO_SMALL
+    tin.Wo = None
+    st = lib.mecefo_block_fwd(C.byref(d), C.byref(a), C.byref(tin), C.byref(tout), ws, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "Wo is NULL" in B.mecefo_last_error()
