@@ -262,6 +262,33 @@ def block_bwd_full(X, dOut, p, heads, batch, seq, eps=1e-6):
     return out
 
 
+# ------------------------------------------------ gradient averaging and optimizer step (Alg. 1)
+def masked_grad_average(grads, contributes):
+    """Eq. (1): mean of the per-rank gradients over the ranks that contribute (for q, k, v, o: the
+    ranks that are neither failed nor neighbors; for the FFN matrices: every rank).  With no
+    contributing rank the paper leaves the result open; the reading here is a zero gradient."""
+    grads = [np.asarray(g, dtype=np.float64) for g in grads]
+    idx = [i for i, c in enumerate(contributes) if c]
+    if not idx:
+        return np.zeros_like(grads[0])
+    acc = np.zeros_like(grads[0])
+    for i in idx:
+        acc = acc + grads[i]
+    return acc / len(idx)
+
+
+def adamw_step(w, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    """One AdamW update with decoupled weight decay (the optimizer of the paper's training
+    configuration); t counts from 1.  Returns the new (w, m, v)."""
+    w, g, m, v = (np.asarray(x, dtype=np.float64) for x in (w, g, m, v))
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** t)
+    vhat = v / (1.0 - beta2 ** t)
+    w = w * (1.0 - lr * weight_decay) - lr * mhat / (np.sqrt(vhat) + eps)
+    return w, m, v
+
+
 # ------------------------------------------------ token-stack harness (inputs only)
 def stack_forward(ids, params, heads, eps=1e-6, dtype=np.float64, keep_last=None):
     """Embedding -> L blocks; returns the stored FFN inputs H_l and the last block's output.

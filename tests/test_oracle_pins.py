@@ -406,3 +406,30 @@ def test_softmax_backward_row_term_equals_output_dot():
     Oh = c["O"].reshape(batch, seq, heads, dh).transpose(0, 2, 1, 3)
     rhs = np.sum(dO * Oh, axis=-1)
     assert np.allclose(lhs, rhs, rtol=1e-12, atol=1e-13)
+
+
+def test_masked_average_reduces_to_plain_mean_and_excludes_masked_ranks():
+    """Eq. (1): with every rank contributing it is the plain mean; a masked rank's values (even
+    non-finite ones) do not enter; the divisor is the number of contributing ranks."""
+    rng = np.random.default_rng(13)
+    G = [rng.standard_normal((5, 7)) for _ in range(4)]
+    assert np.allclose(O.masked_grad_average(G, [1, 1, 1, 1]), np.mean(G, axis=0), rtol=1e-15)
+    G[2][:] = np.nan
+    got = O.masked_grad_average(G, [1, 1, 0, 1])
+    assert np.allclose(got, (G[0] + G[1] + G[3]) / 3.0, rtol=1e-15)
+    assert np.array_equal(O.masked_grad_average(G, [0, 0, 0, 0]), np.zeros((5, 7)))
+    assert np.allclose(O.masked_grad_average(G, [0, 1, 0, 0]), G[1])
+
+
+def test_adamw_matches_torch_optimizer():
+    rng = np.random.default_rng(14)
+    w0 = rng.standard_normal((6, 5))
+    p = torch.nn.Parameter(torch.tensor(w0))
+    opt = torch.optim.AdamW([p], lr=3e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.01)
+    w, m, v = w0.copy(), np.zeros_like(w0), np.zeros_like(w0)
+    for t in range(1, 5):
+        g = rng.standard_normal((6, 5))
+        p.grad = torch.tensor(g)
+        opt.step()
+        w, m, v = O.adamw_step(w, g, m, v, t, 3e-3)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-12, atol=1e-14), t
