@@ -192,6 +192,54 @@ mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_att
     const mecefo_block_fwd_inputs_t* in, const mecefo_block_fwd_outputs_t* out,
     void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- A stack of n_layers identical blocks in neighbor mode (Alg. 2 and Alg. 3 per layer, chained):
+ * the forward keeps H_l of every layer and nothing else; the backward walks the layers from the top,
+ * handing each layer's dX to the layer below as its dOut.  Both only enqueue (HIP-graph capturable:
+ * a whole pass is one launch sequence without host decisions). */
+typedef struct {
+  const void *g_attn, *g_ffn;
+  const void *Wq, *Wk, *Wv, *Wo;     /* unused by the backward: no MHA gradient in neighbor mode */
+  const void *Wg, *Wu, *Wd;
+} mecefo_layer_weights_t;
+
+typedef struct {
+  mecefo_proj_t Pg, Pu, Pd;
+  void *dg_ffn, *dWg, *dWu, *dWd;     /* grad_dtype; dg_ffn may be NULL */
+} mecefo_layer_lowrank_t;
+
+/* X0 [b x d] -> X_out [b x d] (must not alias X0); H[l] [b x d] receives layer l's FFN-module input. */
+mecefo_status_t mecefo_stack_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+    int r_gate, int r_up, int r_down, size_t* out_bytes);
+mecefo_status_t mecefo_stack_fwd_neighbor(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+    int n_layers, const mecefo_layer_weights_t* layers, const void* X0, void* const* H, void* X_out,
+    void* ws, size_t ws_bytes, void* hip_stream);
+/* dOut_top [b x d]: gradient of the last layer's output; dX_bottom [b x d]: gradient of the first
+ * layer's input (may alias dOut_top). */
+mecefo_status_t mecefo_stack_bwd_skip(const mecefo_ffn_desc_t* desc, int n_layers,
+    const mecefo_layer_weights_t* layers, const void* const* H, const mecefo_layer_lowrank_t* lowrank,
+    mecefo_side_t side, const void* dOut_top, void* dX_bottom, int accumulate,
+    void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---- After the backward pass of a layer (Alg. 1): gradient average and optimizer step.
+ * mecefo_grad_average is Eq. (1) on gradient buffers that live on this GPU (the exchange between
+ * ranks is not part of the library): out = mean over the ranks r with contributes[r] != 0 of
+ * grads[r], summed in rank order.  For q, k, v, o those are the ranks that are neither failed nor
+ * neighbors; for gate, up, down every rank.  A rank that does not contribute may pass NULL.
+ * If no rank contributes the result is zero (the paper leaves this case open).
+ * grads: host array of n_ranks (<= 16) device pointers to n_elems elements of grad_dtype each
+ * (padding elements of strided matrices are averaged along); out may alias one of them. */
+mecefo_status_t mecefo_grad_average(mecefo_dtype_t grad_dtype, const void* const* grads,
+    const int32_t* contributes, int n_ranks, void* out, int64_t n_elems, void* hip_stream);
+
+/* AdamW with decoupled weight decay (the paper's training configuration: beta1 0.9, beta2 0.999,
+ * eps 1e-8, weight decay 0.01), step >= 1:
+ *   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
+ *   w = w (1 - lr wd) - lr (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps).
+ * W [n_elems] in w_dtype (updated in place), G in grad_dtype (F32 or w_dtype), M and V fp32. */
+mecefo_status_t mecefo_adamw_step(mecefo_dtype_t w_dtype, mecefo_dtype_t grad_dtype, void* W,
+    const void* G, float* M, float* V, int64_t n_elems, int64_t step, float lr, float beta1,
+    float beta2, float eps, float weight_decay, void* hip_stream);
+
 /* ---- Projection refresh (Alg. 3: every tau neighbor steps the projection of a layer is recomputed
  * from its current weights, W = U S V^T, V1 = the first r columns of V; Sec. 3.4).
  * The call approximates span(V1) on the GEMM core without an SVD or a QR factorisation:

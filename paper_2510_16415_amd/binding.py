@@ -57,6 +57,18 @@ class BlockFwdOutputs(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _FWD_OUT]
 
 
+_LAYER_W = ["g_attn", "g_ffn", "Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd"]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LAYER_W]
+
+
+class LayerLowrank(C.Structure):
+    _fields_ = [("Pg", Proj), ("Pu", Proj), ("Pd", Proj), ("dg_ffn", C.c_void_p), ("dWg", C.c_void_p),
+                ("dWu", C.c_void_p), ("dWd", C.c_void_p)]
+
+
 class MecefoError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"mecefo status {status}: {message}")
@@ -91,6 +103,13 @@ def lib() -> C.CDLL:
     L.mecefo_block_fwd_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(C.c_size_t)]
     L.mecefo_block_fwd.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(BlockFwdInputs), C.POINTER(BlockFwdOutputs),
                                    _vp, C.c_size_t, _vp]
+    L.mecefo_stack_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    L.mecefo_stack_fwd_neighbor.argtypes = [D, C.POINTER(AttnDesc), C.c_int, C.POINTER(LayerWeights), _vp,
+                                            C.POINTER(C.c_void_p), _vp, _vp, C.c_size_t, _vp]
+    L.mecefo_stack_bwd_skip.argtypes = [D, C.c_int, C.POINTER(LayerWeights), C.POINTER(C.c_void_p),
+                                        C.POINTER(LayerLowrank), C.c_int, _vp, _vp, C.c_int, _vp, C.c_size_t, _vp]
+    L.mecefo_grad_average.argtypes = [C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.c_int, _vp, C.c_int64, _vp]
+    L.mecefo_adamw_step.argtypes = [C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int64, C.c_int64] + [C.c_float] * 5 + [_vp]
     L.mecefo_projection_workspace_bytes.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_size_t)]
     L.mecefo_projection_refresh.argtypes = [C.c_int, _vp, C.c_int, C.c_int, C.c_int64, C.c_int, _vp, C.c_int64,
                                             C.c_int, C.c_int, C.c_int, C.c_int, _vp, C.c_int64, _vp, C.c_size_t, _vp]
@@ -101,7 +120,8 @@ def lib() -> C.CDLL:
     for f in ("mecefo_workspace_bytes", "mecefo_ffn_fwd_recompute", "mecefo_ffn_bwd_exact",
               "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip", "mecefo_block_full_workspace_bytes",
               "mecefo_block_bwd_full", "mecefo_projection_workspace_bytes", "mecefo_projection_refresh",
-              "mecefo_block_fwd_workspace_bytes", "mecefo_block_fwd"):
+              "mecefo_block_fwd_workspace_bytes", "mecefo_block_fwd", "mecefo_grad_average", "mecefo_adamw_step",
+              "mecefo_stack_workspace_bytes", "mecefo_stack_fwd_neighbor", "mecefo_stack_bwd_skip"):
         getattr(L, f).restype = C.c_int
     _lib = L
     return L
@@ -215,6 +235,57 @@ def mecefo_block_fwd(desc, attn, inputs: dict, outputs: dict, ws, stream=None):
     p, n = _ws(ws)
     tin, tout = _table(BlockFwdInputs, _FWD_IN, inputs), _table(BlockFwdOutputs, _FWD_OUT, outputs)
     _check(lib().mecefo_block_fwd(C.byref(desc), C.byref(attn), C.byref(tin), C.byref(tout), p, n, _stream(stream)))
+
+
+def mecefo_stack_workspace_bytes(desc, attn, r_gate=0, r_up=0, r_down=0) -> int:
+    out = C.c_size_t(0)
+    _check(lib().mecefo_stack_workspace_bytes(C.byref(desc), C.byref(attn), r_gate, r_up, r_down, C.byref(out)))
+    return out.value
+
+
+def layer_weights(layers):
+    """layers: list of dicts of tensors by the field names of mecefo_layer_weights_t."""
+    return (LayerWeights * len(layers))(*[_table(LayerWeights, _LAYER_W, d) for d in layers])
+
+
+def layer_lowrank(layers):
+    """layers: list of dicts with Pg, Pu, Pd (Proj) and dg_ffn, dWg, dWu, dWd (tensors)."""
+    arr = (LayerLowrank * len(layers))()
+    for a, d in zip(arr, layers):
+        a.Pg, a.Pu, a.Pd = d["Pg"], d["Pu"], d["Pd"]
+        for k in ("dg_ffn", "dWg", "dWu", "dWd"):
+            setattr(a, k, None if d.get(k) is None else d[k].data_ptr())
+    return arr
+
+
+def _ptr_array(tensors):
+    return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def mecefo_stack_fwd_neighbor(desc, attn, layers, X0, H, X_out, ws, stream=None):
+    p, n = _ws(ws)
+    _check(lib().mecefo_stack_fwd_neighbor(C.byref(desc), C.byref(attn), len(layers), layers, _ptr(X0),
+                                           _ptr_array(H), _ptr(X_out), p, n, _stream(stream)))
+
+
+def mecefo_stack_bwd_skip(desc, layers, H, lowrank, side, dOut_top, dX_bottom, accumulate, ws, stream=None):
+    p, n = _ws(ws)
+    _check(lib().mecefo_stack_bwd_skip(C.byref(desc), len(layers), layers, _ptr_array(H), lowrank, int(side),
+                                       _ptr(dOut_top), _ptr(dX_bottom), int(accumulate), p, n, _stream(stream)))
+
+
+def mecefo_grad_average(grad_dtype, grads, contributes, out, n_elems, stream=None):
+    """grads: list of tensors (None allowed for ranks that do not contribute)."""
+    n = len(grads)
+    ptrs = (C.c_void_p * n)(*[None if g is None else g.data_ptr() for g in grads])
+    mask = (C.c_int32 * n)(*[int(bool(c)) for c in contributes])
+    _check(lib().mecefo_grad_average(grad_dtype, ptrs, mask, n, _ptr(out), n_elems, _stream(stream)))
+
+
+def mecefo_adamw_step(w_dtype, grad_dtype, W, G, M, V, n_elems, step, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                      weight_decay=0.01, stream=None):
+    _check(lib().mecefo_adamw_step(w_dtype, grad_dtype, _ptr(W), _ptr(G), _ptr(M), _ptr(V), n_elems, step, lr,
+                                   beta1, beta2, eps, weight_decay, _stream(stream)))
 
 
 def mecefo_projection_workspace_bytes(dtype, m, n, r, left=0) -> int:

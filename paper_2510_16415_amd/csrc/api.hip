@@ -943,4 +943,68 @@ mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_att
   return MECEFO_OK;
 }
 
+mecefo_status_t mecefo_stack_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+                                             int r_gate, int r_up, int r_down, size_t* out_bytes) {
+  size_t fwd = 0, bwd = 0;
+  TRY(mecefo_block_fwd_workspace_bytes(desc, attn, &fwd));
+  TRY(mecefo_workspace_bytes(desc, r_gate, r_up, r_down, &bwd));
+  if (!out_bytes) return fail(MECEFO_ERR_INVALID_ARG, "out_bytes is NULL");
+  // two [b x ld] activation buffers for the forward ping-pong behind the larger of the two workspaces
+  const size_t act = (size_t)up((int64_t)desc->tokens * desc->ld_act_d * (desc->dtype == MECEFO_BF16 ? 2 : 4), 256);
+  *out_bytes = (fwd > bwd ? fwd : bwd) + 2 * act + 512;
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_stack_fwd_neighbor(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+                                          int n_layers, const mecefo_layer_weights_t* layers, const void* X0,
+                                          void* const* H, void* X_out, void* ws, size_t ws_bytes,
+                                          void* hip_stream) {
+  Ctx c;
+  TRY(check_desc(desc, &c));
+  TRY(check_attn(c, attn));
+  if (n_layers < 1) return fail(MECEFO_ERR_INVALID_ARG, "n_layers must be >= 1");
+  if (!layers || !H) return fail(MECEFO_ERR_INVALID_ARG, "layers and H are required");
+  if (c.b > 0 && X_out == X0) return fail(MECEFO_ERR_INVALID_ARG, "X_out must not alias X0");
+  size_t inner = 0;
+  TRY(mecefo_block_fwd_workspace_bytes(desc, attn, &inner));
+  const size_t act = (size_t)up(c.b * desc->ld_act_d * c.esz, 256);
+  if (!ws) return fail(MECEFO_ERR_INVALID_ARG, "workspace is NULL");
+  char* base = (char*)up((int64_t)(uintptr_t)ws, 256);
+  const size_t lead = (size_t)(base - (char*)ws);
+  if (lead + 2 * act + inner > ws_bytes) return fail(MECEFO_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, lead + 2 * act + inner);
+  void* pp[2] = {base, base + act};
+  void* inner_ws = base + 2 * act;
+  const void* x = X0;
+  for (int l = 0; l < n_layers; ++l) {
+    const mecefo_layer_weights_t& w = layers[l];
+    mecefo_block_fwd_inputs_t in = {x, w.g_attn, w.g_ffn, w.Wq, w.Wk, w.Wv, w.Wo, w.Wg, w.Wu, w.Wd};
+    void* y = l == n_layers - 1 ? X_out : pp[l & 1];
+    mecefo_block_fwd_outputs_t out = {y, H[l], nullptr, nullptr, nullptr, nullptr, nullptr};
+    mecefo_status_t st = mecefo_block_fwd(desc, attn, &in, &out, inner_ws, ws_bytes - lead - 2 * act, hip_stream);
+    if (st != MECEFO_OK) return st;
+    x = y;
+  }
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_stack_bwd_skip(const mecefo_ffn_desc_t* desc, int n_layers, const mecefo_layer_weights_t* layers,
+                                      const void* const* H, const mecefo_layer_lowrank_t* lowrank, mecefo_side_t side,
+                                      const void* dOut_top, void* dX_bottom, int accumulate, void* ws,
+                                      size_t ws_bytes, void* hip_stream) {
+  if (n_layers < 1) return fail(MECEFO_ERR_INVALID_ARG, "n_layers must be >= 1");
+  if (!layers || !H || !lowrank) return fail(MECEFO_ERR_INVALID_ARG, "layers, H and lowrank are required");
+  // the gradient travels down in dX_bottom's buffer: every layer overwrites its dOut with its dX
+  const void* g = dOut_top;
+  for (int l = n_layers - 1; l >= 0; --l) {
+    const mecefo_layer_weights_t& w = layers[l];
+    const mecefo_layer_lowrank_t& q = lowrank[l];
+    mecefo_status_t st = mecefo_block_bwd_skip(desc, H[l], g, w.g_ffn, w.Wg, w.Wu, w.Wd, q.Pg, q.Pu, q.Pd, side,
+                                               dX_bottom, q.dg_ffn, q.dWg, q.dWu, q.dWd, accumulate, ws, ws_bytes,
+                                               hip_stream);
+    if (st != MECEFO_OK) return st;
+    g = dX_bottom;
+  }
+  return MECEFO_OK;
+}
+
 }  // extern "C"

@@ -1,0 +1,257 @@
+"""GPU checks of what surrounds the hot path in Alg. 1 / Alg. 2: the neighbor-mode stack (forward
+keeping only H_l, chained degraded backward), Eq. (1) gradient averaging over simulated ranks, the
+AdamW step, and HIP-graph capture of a whole stack pass."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mecefo_oracle as O
+from paper_2510_16415_amd import binding as B
+from paper_2510_16415_amd import inputs as I
+from gpu_util import TOL, dev, host, relerr, tdtype, up8
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-6
+
+
+# ------------------------------------------------------------------ Eq. (1)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mask", [[1, 1, 1, 1], [1, 0, 1, 0], [0, 0, 1, 0], [0, 0, 0, 0]])
+def test_grad_average_matches_eq1(dtype, mask):
+    rng = np.random.default_rng([31, sum(mask)])
+    n = 1000 * 37 + 3                      # not a multiple of the vector width
+    G = [rng.standard_normal(n).astype(np.float32) for _ in range(4)]
+    if dtype == "bf16":
+        G = [I.round_to_bf16_grid(g) for g in G]
+    t = tdtype(dtype)
+    Gd = [torch.from_numpy(g).to(t).cuda() if m else None for g, m in zip(G, mask)]   # masked ranks pass NULL
+    out = torch.full((n,), float("nan"), dtype=t, device="cuda")
+    B.mecefo_grad_average(B.BF16 if dtype == "bf16" else B.F32, Gd, mask, out, n)
+    torch.cuda.synchronize()
+    want = O.masked_grad_average(G, mask)
+    got = out.float().cpu().numpy()
+    if sum(mask) == 0:
+        assert np.array_equal(got, np.zeros(n, dtype=np.float32))
+    else:
+        assert relerr(got, want) < (1e-6 if dtype == "f32" else 4e-3)
+
+
+def test_grad_average_in_place_on_the_first_rank():
+    rng = np.random.default_rng(32)
+    G = [rng.standard_normal(4096).astype(np.float32) for _ in range(3)]
+    Gd = [torch.from_numpy(g).cuda() for g in G]
+    B.mecefo_grad_average(B.F32, Gd, [1, 1, 1], Gd[0], 4096)
+    torch.cuda.synchronize()
+    assert relerr(Gd[0].cpu().numpy(), O.masked_grad_average(G, [1, 1, 1])) < 1e-6
+
+
+# ------------------------------------------------------------------ AdamW
+def f32(x):
+    """The hyper-parameter value the C ABI receives (a float): the oracle is given the same number."""
+    return float(np.float32(x))
+
+
+HP = dict(beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), weight_decay=f32(0.01))
+
+
+def test_adamw_f32_three_steps():
+    rng = np.random.default_rng(33)
+    n = 5003
+    w = rng.standard_normal(n).astype(np.float32)
+    Wd = torch.from_numpy(w.copy()).cuda()
+    M = torch.zeros(n, device="cuda")
+    V = torch.zeros(n, device="cuda")
+    wo, mo, vo = w.astype(np.float64), np.zeros(n), np.zeros(n)
+    for t in range(1, 4):
+        g = rng.standard_normal(n).astype(np.float32)
+        B.mecefo_adamw_step(B.F32, B.F32, Wd, torch.from_numpy(g).cuda(), M, V, n, t, 3e-3)
+        wo, mo, vo = O.adamw_step(wo, g, mo, vo, t, f32(3e-3), **HP)
+    torch.cuda.synchronize()
+    assert relerr(Wd.cpu().numpy(), wo) < 1e-6
+    assert relerr(M.cpu().numpy(), mo) < 1e-6 and relerr(V.cpu().numpy(), vo) < 1e-6
+
+
+def test_adamw_bf16_weights_round_once_per_step():
+    """bf16 parameters: every step is compared from the GPU's own (rounded) weights, so that both
+    sides round the same update; the result must be the oracle's value within one bf16 ulp."""
+    rng = np.random.default_rng(34)
+    n = 4099
+    w = I.round_to_bf16_grid(rng.standard_normal(n).astype(np.float32))
+    Wd = torch.from_numpy(w).to(torch.bfloat16).cuda()
+    M = torch.zeros(n, device="cuda")
+    V = torch.zeros(n, device="cuda")
+    for t in range(1, 4):
+        g = rng.standard_normal(n).astype(np.float32)
+        w_before = Wd.float().cpu().numpy().astype(np.float64)
+        m_before, v_before = M.cpu().numpy().astype(np.float64), V.cpu().numpy().astype(np.float64)
+        B.mecefo_adamw_step(B.BF16, B.F32, Wd, torch.from_numpy(g).cuda(), M, V, n, t, 1e-2)
+        torch.cuda.synchronize()
+        wo, _, _ = O.adamw_step(w_before, g, m_before, v_before, t, f32(1e-2), **HP)
+        got = Wd.float().cpu().numpy()
+        assert np.all(np.abs(got - wo) <= np.abs(wo) * 2.0 ** -8 + 1e-30)
+
+
+# ------------------------------------------------------------------ the stack
+class Stack:
+    def __init__(self, n_layers, batch, seq, d, f, heads, r, dtype, seed):
+        rng = np.random.default_rng([35, seed])
+        self.n_layers, self.dtype, self.heads, self.batch, self.seq = n_layers, dtype, heads, batch, seq
+        self.b, self.d, self.f, self.r = batch * seq, d, f, r
+        self.params = []
+        for _ in range(n_layers):
+            Wg, Wu, Wd, _ = I.ffn_weights(rng, d, f, dtype, std=0.05)
+            Wq, Wk, Wv, Wo, _ = I.mha_weights(rng, d, dtype, std=1.0 / np.sqrt(d))
+            p = dict(Wq=Wq, Wk=Wk, Wv=Wv, Wo=Wo, Wg=Wg, Wu=Wu, Wd=Wd, g_attn=I.perturbed_gain(rng, d, dtype),
+                     g_ffn=I.perturbed_gain(rng, d, dtype))
+            p["P"] = [I.random_orthonormal(rng, d, r, dtype), I.random_orthonormal(rng, d, r, dtype),
+                      I.random_orthonormal(rng, f, r, dtype)]
+            self.params.append(p)
+        self.X0, self.dOut = I.gaussian_block_io(rng, self.b, d, dtype)
+        al = 8 if dtype == "bf16" else 1
+        self.ldf = (f + al - 1) // al * al
+        dt = B.BF16 if dtype == "bf16" else B.F32
+        self.desc = B.make_desc(self.b, d, f, dt, B.F32, d, self.ldf, d, self.ldf, EPS)
+        self.attn = B.make_attn_desc(batch, seq, heads, d)
+        self.dev_layers = []
+        for p in self.params:
+            e = {k: dev(p[k], dtype) for k in ("g_attn", "g_ffn", "Wq", "Wk", "Wv", "Wo", "Wg", "Wu")}
+            e["Wd"] = dev(p["Wd"], dtype, self.ldf)
+            self.dev_layers.append(e)
+        self.lw = B.layer_weights(self.dev_layers)
+        t = tdtype(dtype)
+        self.H = [torch.full((self.b, d), float("nan"), dtype=t, device="cuda") for _ in range(n_layers)]
+        self.X0d, self.dOd = dev(self.X0, dtype), dev(self.dOut, dtype)
+        self.Xout = torch.full((self.b, d), float("nan"), dtype=t, device="cuda")
+        self.dX = torch.full((self.b, d), float("nan"), dtype=t, device="cuda")
+        self.Pdev = [[dev(P, dtype, up8(r) if dtype == "bf16" else r) for P in p["P"]] for p in self.params]
+        self.grads = [dict(dg_ffn=torch.full((d,), float("nan"), device="cuda"),
+                           dWg=torch.full((f, d), float("nan"), device="cuda"),
+                           dWu=torch.full((f, d), float("nan"), device="cuda"),
+                           dWd=torch.full((d, self.ldf), float("nan"), device="cuda")) for _ in range(n_layers)]
+        self.lr = B.layer_lowrank([dict(Pg=B.proj(P[0], r), Pu=B.proj(P[1], r), Pd=B.proj(P[2], r), **g)
+                                   for P, g in zip(self.Pdev, self.grads)])
+        self.ws = torch.empty(B.mecefo_stack_workspace_bytes(self.desc, self.attn, r, r, r), dtype=torch.uint8, device="cuda")
+
+    def forward(self):
+        B.mecefo_stack_fwd_neighbor(self.desc, self.attn, self.lw, self.X0d, self.H, self.Xout, self.ws)
+
+    def backward(self, accumulate=0):
+        B.mecefo_stack_bwd_skip(self.desc, self.lw, self.H, self.lr, B.SIDE_INPUT, self.dOd, self.dX, accumulate, self.ws)
+
+    def oracle(self):
+        x = self.X0.astype(np.float64)
+        Hs = []
+        for p in self.params:
+            x, H, _ = O.block_fwd_full(x, p, self.heads, self.batch, self.seq, EPS)
+            Hs.append(H)
+        g = self.dOut.astype(np.float64)
+        res = [None] * self.n_layers
+        for l in range(self.n_layers - 1, -1, -1):
+            p = self.params[l]
+            res[l] = O.block_bwd_skip(Hs[l], g, p["g_ffn"], p["Wg"], p["Wu"], p["Wd"], *p["P"], EPS)
+            g = res[l]["dX"]
+        return x, Hs, res
+
+    def results(self):
+        torch.cuda.synchronize()
+        return dict(Xout=host(self.Xout), H=[host(h) for h in self.H], dX=host(self.dX),
+                    grads=[dict(dgamma=host(g["dg_ffn"]), dWg=host(g["dWg"]), dWu=host(g["dWu"]),
+                                dWd=host(g["dWd"], self.f)) for g in self.grads])
+
+
+@pytest.mark.parametrize("dtype,n_layers,batch,seq,d,f,heads,r", [("f32", 3, 2, 24, 32, 88, 4, 8),
+                                                                  ("bf16", 4, 2, 128, 128, 344, 4, 32)])
+def test_neighbor_mode_stack_forward_and_chained_backward(dtype, n_layers, batch, seq, d, f, heads, r):
+    st = Stack(n_layers, batch, seq, d, f, heads, r, dtype, 1)
+    st.forward()
+    st.backward()
+    got = st.results()
+    x, Hs, res = st.oracle()
+    tol = TOL[dtype] * (2 if dtype == "bf16" else 10)    # errors of the layers above travel down the chain
+    assert relerr(got["Xout"], x) < tol
+    for l in range(n_layers):
+        assert relerr(got["H"][l], Hs[l]) < tol, l
+        for k in ("dgamma", "dWg", "dWu", "dWd"):
+            assert relerr(got["grads"][l][k], res[l][k]) < tol, (l, k)
+    assert relerr(got["dX"], res[0]["dX"]) < tol
+    print(dtype, "stack: Xout", relerr(got["Xout"], x), "dX", relerr(got["dX"], res[0]["dX"]),
+          "dWg[0]", relerr(got["grads"][0]["dWg"], res[0]["dWg"]))
+
+
+def test_stack_calls_equal_the_per_layer_calls_bit_for_bit():
+    st = Stack(3, 2, 64, 64, 172, 4, 16, "bf16", 2)
+    st.forward()
+    st.backward()
+    a = st.results()
+    # the same chain through the single-block entry points
+    bws = torch.empty(B.mecefo_workspace_bytes(st.desc, st.r, st.r, st.r), dtype=torch.uint8, device="cuda")
+    g = st.dOd.clone()
+    for l in range(2, -1, -1):
+        e, P, G = st.dev_layers[l], st.Pdev[l], st.grads[l]
+        for t in G.values():
+            t.fill_(float("nan"))
+        B.mecefo_block_bwd_skip(st.desc, st.H[l], g, e["g_ffn"], e["Wg"], e["Wu"], e["Wd"], B.proj(P[0], st.r),
+                                B.proj(P[1], st.r), B.proj(P[2], st.r), B.SIDE_INPUT, g, G["dg_ffn"], G["dWg"], G["dWu"],
+                                G["dWd"], 0, bws)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(g), a["dX"])
+    b = st.results()
+    for l in range(3):
+        for k in a["grads"][l]:
+            assert np.array_equal(a["grads"][l][k], b["grads"][l][k]), (l, k)
+
+
+def test_whole_stack_pass_in_one_hip_graph():
+    """Forward + chained backward of the stack captured once and replayed with fresh inputs, with
+    eager work and synchronisations between the replays; every replay must equal the eager pass."""
+    st = Stack(3, 2, 64, 64, 172, 4, 16, "bf16", 3)
+    inputs = [I.gaussian_block_io(np.random.default_rng([36, i]), st.b, st.d, "bf16") for i in range(3)]
+    eager = []
+    for X, dO in inputs:
+        st.X0d.copy_(dev(X, "bf16")); st.dOd.copy_(dev(dO, "bf16"))
+        st.forward(); st.backward()
+        eager.append(st.results())
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        st.forward()
+        st.backward()
+    for i in (1, 2, 0, 2):
+        st.X0d.copy_(dev(inputs[i][0], "bf16")); st.dOd.copy_(dev(inputs[i][1], "bf16"))
+        st.dX.fill_(float("nan")); st.Xout.fill_(float("nan"))
+        for g in st.grads:
+            g["dWg"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = st.results()
+        assert np.array_equal(got["Xout"], eager[i]["Xout"]) and np.array_equal(got["dX"], eager[i]["dX"])
+        for l in range(3):
+            for k in got["grads"][l]:
+                assert np.array_equal(got["grads"][l][k], eager[i]["grads"][l][k]), (i, l, k)
+
+
+def test_one_training_step_two_simulated_ranks():
+    """Alg. 1 for one FFN matrix on two simulated ranks: both run the degraded backward on their own
+    micro-batch, Eq. (1) averages (every rank contributes to an FFN matrix), AdamW updates."""
+    sts = [Stack(1, 2, 24, 32, 88, 4, 8, "f32", 4) for _ in range(2)]
+    rng = np.random.default_rng(37)
+    for st in sts[1:]:                      # same weights, different data
+        X, dO = I.gaussian_block_io(rng, st.b, st.d, "f32")
+        st.X0, st.dOut = X, dO
+        st.X0d.copy_(dev(X, "f32")); st.dOd.copy_(dev(dO, "f32"))
+    want_g = []
+    for st in sts:
+        st.forward(); st.backward()
+        want_g.append(st.oracle()[2][0]["dWg"])
+    n = sts[0].f * sts[0].d
+    avg = torch.empty(sts[0].f, sts[0].d, device="cuda")
+    B.mecefo_grad_average(B.F32, [st.grads[0]["dWg"] for st in sts], [1, 1], avg, n)
+    W = sts[0].dev_layers[0]["Wg"].clone()
+    M, V = torch.zeros_like(W), torch.zeros_like(W)
+    B.mecefo_adamw_step(B.F32, B.F32, W, avg, M, V, n, 1, 1e-3)
+    torch.cuda.synchronize()
+    g = O.masked_grad_average(want_g, [1, 1])
+    w, _, _ = O.adamw_step(sts[0].params[0]["Wg"], g, np.zeros_like(g), np.zeros_like(g), 1, f32(1e-3), **HP)
+    assert relerr(avg.cpu().numpy(), g) < 1e-5
+    assert relerr(W.cpu().numpy(), w) < 1e-6
