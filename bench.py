@@ -184,6 +184,8 @@ def main():
                                               dWg, dWu, dWd, ws, ms_per_step, cfg)
     if not args.no_overhead:
         out["projection_refresh"] = projection_refresh(B, torch, Wg, Wd, Pg, Pd, d, f, ldf, r, ms_per_step)
+    if not args.no_overhead:
+        out["neighbor_stack"] = neighbor_stack(B, torch, I)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
@@ -298,6 +300,84 @@ def projection_refresh(B, torch, Wg, Wd, Pg, Pd, d, f, ldf, r, deg_block_ms, tau
     res["amortised_ms_per_step_tau100_warm"] = round(per_step, 4)
     res["amortised_fraction_of_degraded_block"] = round(per_step / deg_block_ms, 4)
     return res
+
+
+def neighbor_stack(B, torch, I, name="C2"):
+    """A whole neighbor-mode pass over the layers of a small stack config (launch-bound): forward keeping
+    only H_l, then the chained degraded backward, eager and replayed from one HIP graph; plus the
+    activation bytes each mode keeps per layer."""
+    cfg = I.CONFIGS[name]
+    dev = torch.device("cuda:0")
+    b, d, f, r, L = cfg.tokens, cfg.d_model, cfg.d_ff, cfg.rank, cfg.layers
+    ldf = (f + 7) // 8 * 8
+    bf = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(777 + cfg.index)
+
+    def rn(rows, cols, std=1.0, ld=None):
+        t = torch.zeros(rows, ld or cols, dtype=bf, device=dev)
+        t[:, :cols] = (torch.randn(rows, cols, generator=gen, device=dev) * std).to(bf)
+        return t
+
+    desc = B.make_desc(b, d, f, B.BF16, B.F32, d, ldf, d, ldf)
+    attn = B.make_attn_desc(cfg.batch, cfg.seq, cfg.heads, d)
+    layers, low, keep = [], [], []
+    for _ in range(L):
+        e = dict(g_attn=torch.ones(d, dtype=bf, device=dev), g_ffn=torch.ones(d, dtype=bf, device=dev),
+                 Wq=rn(d, d, d ** -0.5), Wk=rn(d, d, d ** -0.5), Wv=rn(d, d, d ** -0.5), Wo=rn(d, d, d ** -0.5),
+                 Wg=rn(f, d, 0.02), Wu=rn(f, d, 0.02), Wd=rn(d, f, 0.02, ldf))
+        P = [rn(d, r, d ** -0.5), rn(d, r, d ** -0.5), rn(f, r, f ** -0.5)]
+        g = dict(dg_ffn=torch.zeros(d, device=dev), dWg=torch.zeros(f, d, device=dev),
+                 dWu=torch.zeros(f, d, device=dev), dWd=torch.zeros(d, ldf, device=dev))
+        keep.append((e, P, g))
+        layers.append(e)
+        low.append(dict(Pg=B.proj(P[0], r), Pu=B.proj(P[1], r), Pd=B.proj(P[2], r), **g))
+    lw, lr = B.layer_weights(layers), B.layer_lowrank(low)
+    H = [torch.empty(b, d, dtype=bf, device=dev) for _ in range(L)]
+    X0, dOut = rn(b, d), rn(b, d)
+    Xout, dX = torch.empty_like(X0), torch.empty_like(X0)
+    ws = torch.empty(B.mecefo_stack_workspace_bytes(desc, attn, r, r, r), dtype=torch.uint8, device=dev)
+
+    def fwd():
+        B.mecefo_stack_fwd_neighbor(desc, attn, lw, X0, H, Xout, ws)
+
+    def bwd():
+        B.mecefo_stack_bwd_skip(desc, lw, H, lr, B.SIDE_INPUT, dOut, dX, 0, ws)
+
+    def timed(fn, n=20):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / n
+
+    t_fwd, t_bwd = timed(fwd), timed(bwd)
+    graphs = []
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    for fn in (fwd, bwd):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            fn()
+        graphs.append(g)
+    torch.cuda.current_stream().wait_stream(side)
+    g_fwd, g_bwd = timed(graphs[0].replay), timed(graphs[1].replay)
+    dh = d // cfg.heads
+    kept_neighbor = b * d * 2
+    kept_standard = 5 * b * d * 2 + cfg.batch * cfg.heads * cfg.seq * 4
+    return {
+        "config": f"{name}: {L} layers, tokens={b}, d={d}, f={f}, heads={cfg.heads}, r={r}, bf16",
+        "fwd_eager_ms": round(t_fwd, 4), "fwd_graph_ms": round(g_fwd, 4),
+        "bwd_skip_eager_ms": round(t_bwd, 4), "bwd_skip_graph_ms": round(g_bwd, 4),
+        "bwd_tokens_per_s_graph": round(b / (g_bwd * 1e-3), 1),
+        "activation_bytes_kept_per_layer": {
+            "neighbor_mode_H_only": kept_neighbor,
+            "standard_mode_H_Q_K_V_O_L": kept_standard,
+            "standard_mode_with_saved_G_Z": kept_standard + 2 * b * ldf * 2,
+        },
+    }
 
 
 def cpu_baseline(cfg):
