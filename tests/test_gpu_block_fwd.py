@@ -104,6 +104,15 @@ def test_config_c2_block_fwd():
     print("C2 fwd", run_fwd(27, cfg.batch, cfg.seq, cfg.d_model, cfg.d_ff, cfg.heads, cfg.dtype)[-1])
 
 
-def test_config_c5_block_fwd_one_sequence():
+def test_config_c5_block_fwd_whole_batch():
+    """The 7B-shaped layer at its full batch (4 x 2048 tokens); the oracle walks it one sequence at a time."""
     cfg = I.CONFIGS["C5"]
-    print("C5 fwd", run_fwd(28, 1, cfg.seq, cfg.d_model, cfg.d_ff, cfg.heads, cfg.dtype)[-1])
+    heads, batch, seq, d = cfg.heads, cfg.batch, cfg.seq, cfg.d_model
+    p, X, dOut = make_case(28, batch, seq, d, cfg.d_ff, heads, cfg.dtype)
+    parts = [oracle_forward(p, X[i * seq:(i + 1) * seq], heads, 1, seq) for i in range(batch)]
+    want = {k: np.concatenate([q[k] for q in parts]) for k in parts[0]}
+    blk = FullBlock.__new__(FullBlock)
+    blk.init_from_saved(p, X, dOut, want, heads, batch, seq, cfg.dtype)
+    fwd = Forward(blk, heads, batch, seq)
+    got = fwd.run()
+    print("C5 fwd, whole batch", assert_close(got, want, TOL["bf16"], label="C5 fwd: "))

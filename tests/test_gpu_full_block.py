@@ -39,19 +39,24 @@ class FullBlock:
     """Device buffers, descriptors and workspace for one call of mecefo_block_bwd_full."""
 
     def __init__(self, p, X, dOut, heads, batch, seq, dtype, grad_dtype="f32", pad=0):
+        _, H, cache = O.block_fwd_full(X, p, heads, batch, seq, EPS)
+        b, d = X.shape
+        saved = dict(H=H, Q=token_major(cache["Q"], b, d), K=token_major(cache["K"], b, d),
+                     V=token_major(cache["V"], b, d), O=cache["O"], L=cache["L"].reshape(-1))
+        self.init_from_saved(p, X, dOut, saved, heads, batch, seq, dtype, grad_dtype, pad)
+
+    def init_from_saved(self, p, X, dOut, saved, heads, batch, seq, dtype, grad_dtype="f32", pad=0):
         b, d = X.shape
         f = p["Wg"].shape[0]
         self.b, self.d, self.f, self.dtype = b, d, f, dtype
         al = 8 if dtype == "bf16" else 1
         rnd = (lambda x: (x + al - 1) // al * al)
         self.ld_d, self.ld_f = rnd(d) + pad, rnd(f) + pad
-        _, H, cache = O.block_fwd_full(X, p, heads, batch, seq, EPS)
         cast = (lambda a: I.round_to_bf16_grid(a.astype(np.float32))) if dtype == "bf16" else (lambda a: a.astype(np.float32))
-        self.saved = dict(H=cast(H), Q=cast(token_major(cache["Q"], b, d)), K=cast(token_major(cache["K"], b, d)),
-                          V=cast(token_major(cache["V"], b, d)), O=cast(cache["O"]))
+        self.saved = {k: cast(saved[k]) for k in ("H", "Q", "K", "V", "O")}
         act = lambda a: dev(a, dtype, self.ld_d)
         self.inp = dict(X=act(X), dOut=act(dOut), g_attn=dev(p["g_attn"], dtype), g_ffn=dev(p["g_ffn"], dtype),
-                        L=torch.from_numpy(cache["L"].astype(np.float32).reshape(-1)).cuda())
+                        L=torch.from_numpy(saved["L"].astype(np.float32)).cuda())
         for k, v in self.saved.items():
             self.inp[k] = act(v)
         for k in ("Wq", "Wk", "Wv", "Wo", "Wg", "Wu"):
@@ -182,9 +187,42 @@ def test_config_c2_full_block():
     print("C2 full block", errs)
 
 
-def test_config_c5_full_block_one_sequence():
-    """The 7B-shaped layer at its real d, f, heads and sequence length, one sequence of the batch
-    (the fp64 oracle's attention tensors for one sequence already take several GiB)."""
+def oracle_bwd_full_by_sequence(X, dOut, p, heads, batch, seq):
+    """block_bwd_full of a batch as the sum over its sequences (attention never mixes sequences):
+    keeps the fp64 attention tensors of one sequence in memory at a time."""
+    total = None
+    for i in range(batch):
+        sl = slice(i * seq, (i + 1) * seq)
+        g = O.block_bwd_full(X[sl], dOut[sl], p, heads, 1, seq, EPS)
+        if total is None:
+            total = {k: (np.zeros((batch * seq, X.shape[1])) if k in ("dX", "dH", "dX_branch") else np.zeros_like(v))
+                     for k, v in g.items()}
+        for k, v in g.items():
+            if k in ("dX", "dH", "dX_branch"):
+                total[k][sl] = v
+            else:
+                total[k] += v
+    return total
+
+
+def test_config_c5_full_block_whole_batch():
+    """The 7B-shaped layer exactly as bench.py times it (4 sequences of 2048 tokens, d = 4096,
+    f = 11008, 32 heads); the oracle walks the batch one sequence at a time."""
     cfg = I.CONFIGS["C5"]
-    _, _, errs = run_case(15, 1, cfg.seq, cfg.d_model, cfg.d_ff, cfg.heads, cfg.dtype)
-    print("C5 full block", errs)
+    heads, batch, seq = cfg.heads, cfg.batch, cfg.seq
+    p, X, dOut = make_case(15, batch, seq, cfg.d_model, cfg.d_ff, heads, cfg.dtype)
+    saved = dict(H=[], Q=[], K=[], V=[], O=[], L=[])
+    for i in range(batch):       # forward of the oracle, per sequence
+        sl = slice(i * seq, (i + 1) * seq)
+        _, H, c = O.block_fwd_full(X[sl], p, heads, 1, seq, EPS)
+        saved["H"].append(H)
+        for k in ("Q", "K", "V"):
+            saved[k].append(token_major(c[k], seq, cfg.d_model))
+        saved["O"].append(c["O"])
+        saved["L"].append(c["L"].reshape(-1))
+    blk = FullBlock.__new__(FullBlock)
+    blk.init_from_saved(p, X, dOut, {k: np.concatenate(v) for k, v in saved.items()}, heads, batch, seq, cfg.dtype)
+    want = oracle_bwd_full_by_sequence(X, dOut, p, heads, batch, seq)
+    got = blk.run()
+    errs = assert_close(got, want, TOL["bf16"], keys=["dX"] + GRADS, label="C5 whole batch: ")
+    print("C5 full block, whole batch", errs)
