@@ -185,6 +185,8 @@ def main():
     if not args.no_overhead:
         out["projection_refresh"] = projection_refresh(B, torch, Wg, Wd, Pg, Pd, d, f, ldf, r, ms_per_step)
     if not args.no_overhead:
+        out["variants"] = variants(B, torch, desc, b, d, f, r, ldf, H, dOut, gamma, Wg, Wu, Wd, (Pg, Pu, Pd), dX,
+                                   dgamma, dWg, dWu, dWd)
         out["neighbor_stack"] = neighbor_stack(B, torch, I)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
@@ -299,6 +301,43 @@ def projection_refresh(B, torch, Wg, Wd, Pg, Pd, d, f, ldf, r, deg_block_ms, tau
     per_step = (2 * res["gate_up_warm_2_rounds_ms"] + res["down_warm_2_rounds_ms"]) / tau
     res["amortised_ms_per_step_tau100_warm"] = round(per_step, 4)
     res["amortised_fraction_of_degraded_block"] = round(per_step / deg_block_ms, 4)
+    return res
+
+
+def variants(B, torch, desc, b, d, f, r, ldf, H, dOut, gamma, Wg, Wu, Wd, Ps, dX, dgamma, dWg, dWu, dWd):
+    """The knobs the paper names (extra checkpoints, no low-rank approximation, other ranks), timed with
+    mecefo_block_bwd_skip_ex on the same layer; ms per call."""
+    dev = H.device
+    bf = torch.bfloat16
+
+    def timed(fn, n=10):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / n
+
+    res = {}
+    G = torch.empty(b, ldf, dtype=bf, device=dev)
+    Z = torch.empty_like(G)
+    A = torch.empty_like(G)
+    U = torch.empty_like(H)
+    ws0 = torch.empty(B.mecefo_workspace_bytes(desc, r, r, r), dtype=torch.uint8, device=dev)
+    B.mecefo_ffn_fwd_recompute(desc, H, Wg, Wu, None, G, Z, A, None, ws0)     # values only need to be finite
+    del A, U
+
+    def call(ranks, ws, **kw):
+        Pr = [B.proj(P, rk) if rk else None for P, rk in zip(Ps, ranks)]
+        return lambda: B.mecefo_block_bwd_skip_ex(desc, H, dOut, gamma, Wg, Wu, Wd, *Pr, B.SIDE_INPUT, dX, dgamma,
+                                                  dWg, dWu, dWd, 0, ws, **kw)
+
+    res["default_r%d_ms" % r] = round(timed(call((r, r, r), ws0)), 4)
+    res["saved_G_Z_r%d_ms" % r] = round(timed(call((r, r, r), ws0, G=G, Z=Z)), 4)
+    res["exact_wgrad_all_ms"] = round(timed(call((0, 0, 0), ws0, exact_wgrad_mask=7)), 4)
+    for rk in (r // 4, r // 2):
+        res["default_r%d_ms" % rk] = round(timed(call((rk, rk, rk), ws0)), 4)
     return res
 
 

@@ -261,6 +261,29 @@ mecefo_status_t mecefo_projection_refresh(mecefo_dtype_t dtype, const void* W, i
     int left, const void* V0, int64_t ldv, int r, int power_iters, int cond_steps, int polish_steps,
     void* P, int64_t ldp, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- Tunable variants of the neighbor branch (Sec. 5, extension paragraph: the skip, the
+ * recomputation depth and the rank are knobs).  mecefo_block_bwd_skip_ex is mecefo_block_bwd_skip
+ * with two options; opt == NULL or all-zero options give exactly mecefo_block_bwd_skip.
+ *   G, Z [b x f] (ld_act_f): extra checkpoints.  When given, the gate and up projections kept by
+ *     the forward pass are used and the recompute GEMM is not run (b*f*2 more elements kept per
+ *     layer, 4bdf fewer FLOPs).
+ *   exact_wgrad_mask: bit 0 gate, bit 1 up, bit 2 down: those matrices get the exact weight
+ *     gradient G_y^T x instead of Eq. (2) (their mecefo_proj_t argument is ignored).  Mask 7 is the
+ *     skip-connection and recomputation without the low-rank approximation.
+ * The rank itself is per matrix in the mecefo_proj_t arguments. */
+typedef struct {
+  const void *G, *Z;
+  int32_t exact_wgrad_mask;
+} mecefo_skip_options_t;
+
+mecefo_status_t mecefo_block_bwd_skip_ex(const mecefo_ffn_desc_t* desc, const void* H,
+    const void* dOut, const void* gamma,
+    const void* Wg, const void* Wu, const void* Wd,
+    mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+    const mecefo_skip_options_t* opt,
+    void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
+    void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Measurement aid (not part of the hot path; the only calls that create HIP objects).
  * After mecefo_profile_enable(n) every kernel stage enqueued by the calls above is bracketed
  * by a pair of HIP events on the call's own stream, for at most n stage launches.

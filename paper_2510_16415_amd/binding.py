@@ -69,6 +69,10 @@ class LayerLowrank(C.Structure):
                 ("dWu", C.c_void_p), ("dWd", C.c_void_p)]
 
 
+class SkipOptions(C.Structure):
+    _fields_ = [("G", C.c_void_p), ("Z", C.c_void_p), ("exact_wgrad_mask", C.c_int32)]
+
+
 class MecefoError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"mecefo status {status}: {message}")
@@ -97,6 +101,8 @@ def lib() -> C.CDLL:
                                          [C.c_int, _vp, C.c_size_t, _vp])
     L.mecefo_block_bwd_skip.argtypes = ([D] + [_vp] * 6 + [Proj] * 3 + [C.c_int] + [_vp] * 5 +
                                         [C.c_int, _vp, C.c_size_t, _vp])
+    L.mecefo_block_bwd_skip_ex.argtypes = ([D] + [_vp] * 6 + [Proj] * 3 + [C.c_int, C.POINTER(SkipOptions)] + [_vp] * 5 +
+                                           [C.c_int, _vp, C.c_size_t, _vp])
     L.mecefo_block_full_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(C.c_size_t)]
     L.mecefo_block_bwd_full.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(BlockInputs), C.POINTER(BlockGrads),
                                         C.c_int, _vp, C.c_size_t, _vp]
@@ -121,7 +127,8 @@ def lib() -> C.CDLL:
               "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip", "mecefo_block_full_workspace_bytes",
               "mecefo_block_bwd_full", "mecefo_projection_workspace_bytes", "mecefo_projection_refresh",
               "mecefo_block_fwd_workspace_bytes", "mecefo_block_fwd", "mecefo_grad_average", "mecefo_adamw_step",
-              "mecefo_stack_workspace_bytes", "mecefo_stack_fwd_neighbor", "mecefo_stack_bwd_skip"):
+              "mecefo_stack_workspace_bytes", "mecefo_stack_fwd_neighbor", "mecefo_stack_bwd_skip",
+              "mecefo_block_bwd_skip_ex"):
         getattr(L, f).restype = C.c_int
     _lib = L
     return L
@@ -191,6 +198,17 @@ def mecefo_block_bwd_skip(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX
     _check(lib().mecefo_block_bwd_skip(C.byref(desc), _ptr(H), _ptr(dOut), _ptr(gamma), _ptr(Wg), _ptr(Wu),
                                        _ptr(Wd), Pg, Pu, Pd, int(side), _ptr(dX), _ptr(dgamma), _ptr(dWg),
                                        _ptr(dWu), _ptr(dWd), int(accumulate), p, n, _stream(stream)))
+
+
+def mecefo_block_bwd_skip_ex(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX, dgamma, dWg, dWu, dWd,
+                             accumulate, ws, G=None, Z=None, exact_wgrad_mask=0, stream=None):
+    p, n = _ws(ws)
+    opt = SkipOptions(None if G is None else G.data_ptr(), None if Z is None else Z.data_ptr(), exact_wgrad_mask)
+    null = Proj(None, 0, 0)
+    _check(lib().mecefo_block_bwd_skip_ex(C.byref(desc), _ptr(H), _ptr(dOut), _ptr(gamma), _ptr(Wg), _ptr(Wu),
+                                          _ptr(Wd), Pg or null, Pu or null, Pd or null, int(side), C.byref(opt),
+                                          _ptr(dX), _ptr(dgamma), _ptr(dWg), _ptr(dWu), _ptr(dWd), int(accumulate),
+                                          p, n, _stream(stream)))
 
 
 def make_attn_desc(batch, seq, heads, ld_w_dd, rope_theta=10000.0) -> AttnDesc:

@@ -275,7 +275,7 @@ mecefo_status_t recompute_and_dgrad(const Ctx& c, const Bufs& bf, const void* U,
 // gate: (Gy, X) = (dG, U); up: (dZ, U); down: (dY, A).
 mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64_t ldu, const void* dY,
                               int64_t lddy, const mecefo_proj_t P[3], mecefo_side_t side, void* dW[3],
-                              int accumulate, hipStream_t s) {
+                              int accumulate, hipStream_t s, int exact_mask = 0) {
   const mecefo_ffn_desc_t& d = *c.d;
   char* base = bf.base;
   const int b = (int)c.b;
@@ -291,33 +291,53 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
   void* T[3];
   void* C[3];
   for (int i = 0; i < 3; ++i) { ldt[i] = up(P[i].r, 8); T[i] = base + bf.w.T[i]; C[i] = base + bf.w.C[i]; }
+  // matrices that take Eq. (2) and matrices that take the exact weight gradient
+  int lr[3], ex[3], n_lr = 0, n_ex = 0;
+  for (int i = 0; i < 3; ++i) {
+    if (exact_mask & (1 << i)) ex[n_ex++] = i;
+    else lr[n_lr++] = i;
+  }
+
+  if (n_ex > 0) {  // exact Wgrad: dW = Gy^T X, contraction over tokens
+    STAGE(MECEFO_STAGE_WGRAD_EXACT, s);
+    GemmLaunch g = new_launch(c, false, false, EPI_GRAD);
+    g.nprob = n_ex;
+    g.accumulate = accumulate;
+    for (int j = 0; j < n_ex; ++j) {
+      const int i = ex[j];
+      g.p[j] = prob(Gy[i], nullptr, ldgy[i], X[i], nullptr, ldx[i], dW[i], nullptr, nullptr, lddw[i], m_out[i], n_in[i], b, 1);
+    }
+    HIP_TRY(launch_gemm(g, s));
+  }
+  if (n_lr == 0) return MECEFO_OK;
 
   if (b > 0) {  // project: T = (X or Gy) P, contraction over the projected dimension
     STAGE(MECEFO_STAGE_PROJECT, s);
     GemmLaunch g = new_launch(c, true, false, EPI_STORE);
-    g.nprob = 3;
-    for (int i = 0; i < 3; ++i)
-    {
-      g.p[i] = prob(in ? X[i] : Gy[i], nullptr, in ? ldx[i] : ldgy[i], P[i].P, nullptr, P[i].ld, T[i], nullptr,
+    g.nprob = n_lr;
+    for (int j = 0; j < n_lr; ++j) {
+      const int i = lr[j];
+      g.p[j] = prob(in ? X[i] : Gy[i], nullptr, in ? ldx[i] : ldgy[i], P[i].P, nullptr, P[i].ld, T[i], nullptr,
                     nullptr, ldt[i], b, P[i].r, in ? n_in[i] : m_out[i], 1);
       // the K-contiguous operand is one of the library's own zero-padded [b x f] buffers (A, dG, dZ)
       const void* a_op = in ? X[i] : Gy[i];
-      g.p[i].kpad_ok = (a_op == base + bf.w.AA || a_op == base + bf.w.DG || a_op == base + bf.w.DZ) ? 1 : 0;
+      g.p[j].kpad_ok = (a_op == base + bf.w.AA || a_op == base + bf.w.DG || a_op == base + bf.w.DZ) ? 1 : 0;
     }
     HIP_TRY(launch_gemm(g, s));
   }
   {  // contract over tokens: C = (Gy or X)^T T   [rows x r], K = b
     const int splits = b > 0 ? bf.w.splits : 1;
     GemmLaunch g = new_launch(c, false, false, splits > 1 ? EPI_SPLIT_F32 : EPI_STORE);
-    g.nprob = 3;
+    g.nprob = n_lr;
     g.splits = splits;
     g.partial = (float*)(base + bf.w.partial);
     int64_t poff = 0;
-    for (int i = 0; i < 3; ++i) {
+    for (int j = 0; j < n_lr; ++j) {
+      const int i = lr[j];
       const int rows = in ? m_out[i] : n_in[i];
-      g.p[i] = prob(in ? Gy[i] : X[i], nullptr, in ? ldgy[i] : ldx[i], T[i], nullptr, ldt[i], C[i], nullptr,
+      g.p[j] = prob(in ? Gy[i] : X[i], nullptr, in ? ldgy[i] : ldx[i], T[i], nullptr, ldt[i], C[i], nullptr,
                     nullptr, ldt[i], rows, P[i].r, b, 1);
-      g.partial_off[i] = poff;
+      g.partial_off[j] = poff;
       poff += (int64_t)splits * rows * ldt[i];
     }
     {
@@ -326,23 +346,26 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
     }
     if (splits > 1) {
       STAGE(MECEFO_STAGE_SPLITK_REDUCE, s);
-      // partial of problem i is [split][rows x ldt]; the reduction keeps that row stride
-      for (int i = 0; i < 3; ++i) {
+      // partial of problem j is [split][rows x ldt]; the reduction keeps that row stride
+      for (int j = 0; j < n_lr; ++j) {
+        const int i = lr[j];
         const int rows = in ? m_out[i] : n_in[i];
-        HIP_TRY(launch_splitk_reduce(c.bf16, g.partial + g.partial_off[i], splits, (int64_t)rows * ldt[i], C[i], s));
+        HIP_TRY(launch_splitk_reduce(c.bf16, g.partial + g.partial_off[j], splits, (int64_t)rows * ldt[i], C[i], s));
       }
     }
   }
   {  // expand: dW = C P^T (SIDE_INPUT) or P C^T (SIDE_OUTPUT), K = r, into the gradient buffers
     STAGE(MECEFO_STAGE_EXPAND, s);
     GemmLaunch g = new_launch(c, true, true, EPI_GRAD);
-    g.nprob = 3;
+    g.nprob = n_lr;
     g.accumulate = accumulate;
-    for (int i = 0; i < 3; ++i)
-      g.p[i] = in ? prob(C[i], nullptr, ldt[i], P[i].P, nullptr, P[i].ld, dW[i], nullptr, nullptr, lddw[i],
+    for (int j = 0; j < n_lr; ++j) {
+      const int i = lr[j];
+      g.p[j] = in ? prob(C[i], nullptr, ldt[i], P[i].P, nullptr, P[i].ld, dW[i], nullptr, nullptr, lddw[i],
                          m_out[i], n_in[i], P[i].r, 1)
                   : prob(P[i].P, nullptr, P[i].ld, C[i], nullptr, ldt[i], dW[i], nullptr, nullptr, lddw[i],
                          m_out[i], n_in[i], P[i].r, 1);
+    }
     HIP_TRY(launch_gemm(g, s));
   }
   return MECEFO_OK;
@@ -435,12 +458,12 @@ FwdWs fwd_layout(const Ctx& c, const mecefo_attn_desc_t& a) {
   return w;
 }
 
-mecefo_status_t check_lowrank_args(const Ctx& c, const mecefo_proj_t P[3], mecefo_side_t side) {
+mecefo_status_t check_lowrank_args(const Ctx& c, const mecefo_proj_t P[3], mecefo_side_t side, int exact_mask = 0) {
   if (side != MECEFO_SIDE_INPUT && side != MECEFO_SIDE_OUTPUT) return fail(MECEFO_ERR_INVALID_ARG, "side must be MECEFO_SIDE_INPUT or MECEFO_SIDE_OUTPUT");
   const bool in = side == MECEFO_SIDE_INPUT;
-  TRY(check_proj(c, P[0], in ? c.dm : c.ff, "Pg"));
-  TRY(check_proj(c, P[1], in ? c.dm : c.ff, "Pu"));
-  TRY(check_proj(c, P[2], in ? c.ff : c.dm, "Pd"));
+  if (!(exact_mask & 1)) TRY(check_proj(c, P[0], in ? c.dm : c.ff, "Pg"));
+  if (!(exact_mask & 2)) TRY(check_proj(c, P[1], in ? c.dm : c.ff, "Pu"));
+  if (!(exact_mask & 4)) TRY(check_proj(c, P[2], in ? c.ff : c.dm, "Pd"));
   return MECEFO_OK;
 }
 
@@ -577,13 +600,20 @@ mecefo_status_t mecefo_ffn_bwd_lowrank(const mecefo_ffn_desc_t* desc, const void
   return lowrank_wgrad(c, bf, U, desc->ld_act_d, dY, desc->ld_act_d, P, side, dW, accumulate, s);
 }
 
-mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void* H, const void* dOut,
-                                      const void* gamma, const void* Wg, const void* Wu, const void* Wd,
-                                      mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
-                                      void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
-                                      void* ws, size_t ws_bytes, void* hip_stream) {
+mecefo_status_t mecefo_block_bwd_skip_ex(const mecefo_ffn_desc_t* desc, const void* H, const void* dOut,
+                                         const void* gamma, const void* Wg, const void* Wu, const void* Wd,
+                                         mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+                                         const mecefo_skip_options_t* opt, void* dX, void* dgamma, void* dWg,
+                                         void* dWu, void* dWd, int accumulate, void* ws, size_t ws_bytes,
+                                         void* hip_stream) {
   Ctx c;
   TRY(check_desc(desc, &c));
+  const void* Gs = opt ? opt->G : nullptr;
+  const void* Zs = opt ? opt->Z : nullptr;
+  const int exact_mask = opt ? opt->exact_wgrad_mask : 0;
+  if (exact_mask & ~7) return fail(MECEFO_ERR_INVALID_ARG, "exact_wgrad_mask has bits beyond gate (1), up (2), down (4)");
+  if ((Gs == nullptr) != (Zs == nullptr)) return fail(MECEFO_ERR_INVALID_ARG, "G and Z must both be given or both be NULL");
+  TRY(check_ptr(c, Gs, "G", false)); TRY(check_ptr(c, Zs, "Z", false));
   TRY(check_ptr(c, H, "H", c.b > 0)); TRY(check_ptr(c, dOut, "dOut", c.b > 0)); TRY(check_ptr(c, gamma, "gamma", false));
   TRY(check_ptr(c, Wg, "Wg")); TRY(check_ptr(c, Wu, "Wu")); TRY(check_ptr(c, Wd, "Wd"));
   TRY(check_ptr(c, dX, "dX", c.b > 0));
@@ -591,8 +621,8 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
   if (c.bf16 && (((uintptr_t)dWg | (uintptr_t)dWu | (uintptr_t)dWd) % 16)) return fail(MECEFO_ERR_INVALID_ARG, "gradient buffers must be 16-byte aligned");
   if (dgamma && !gamma) return fail(MECEFO_ERR_INVALID_ARG, "dgamma requested but gamma is NULL");
   const mecefo_proj_t P[3] = {Pg, Pu, Pd};
-  TRY(check_lowrank_args(c, P, side));
-  const int r[3] = {Pg.r, Pu.r, Pd.r};
+  TRY(check_lowrank_args(c, P, side, exact_mask));
+  const int r[3] = {(exact_mask & 1) ? 0 : Pg.r, (exact_mask & 2) ? 0 : Pu.r, (exact_mask & 4) ? 0 : Pd.r};
   Bufs bf;
   TRY(carve(c, r, side, ws, ws_bytes, &bf));
   hipStream_t s = (hipStream_t)hip_stream;
@@ -607,10 +637,10 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
     ldu = c.dm;
   }
   void* dUb = base + bf.w.dU;
-  TRY(recompute_and_dgrad(c, bf, U, ldu, dOut, desc->ld_act_d, Wg, Wu, Wd, nullptr, nullptr, dUb, c.dm, s));
+  TRY(recompute_and_dgrad(c, bf, U, ldu, dOut, desc->ld_act_d, Wg, Wu, Wd, Gs, Zs, dUb, c.dm, s));
   // Eq. (2) reads dOut (as the down projection's output gradient), so it runs before dX may overwrite dOut.
   void* dW[3] = {dWg, dWu, dWd};
-  TRY(lowrank_wgrad(c, bf, U, ldu, dOut, desc->ld_act_d, P, side, dW, accumulate, s));
+  TRY(lowrank_wgrad(c, bf, U, ldu, dOut, desc->ld_act_d, P, side, dW, accumulate, s, exact_mask));
   // Skip the MHA connection: the gradient handed to the previous layer is dH = dOut + normbwd(dU).
   STAGE(MECEFO_STAGE_NORM_BWD, s);
   if (gamma) {
@@ -624,6 +654,15 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
     HIP_TRY(launch_add(c.bf16, dOut, desc->ld_act_d, dUb, c.dm, dX, desc->ld_act_d, c.b, c.dm, s));
   }
   return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void* H, const void* dOut,
+                                      const void* gamma, const void* Wg, const void* Wu, const void* Wd,
+                                      mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+                                      void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
+                                      void* ws, size_t ws_bytes, void* hip_stream) {
+  return mecefo_block_bwd_skip_ex(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, nullptr, dX, dgamma, dWg, dWu,
+                                  dWd, accumulate, ws, ws_bytes, hip_stream);
 }
 
 mecefo_status_t mecefo_block_full_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
