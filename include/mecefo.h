@@ -11,6 +11,9 @@
  *   - Sec. 3.3 (selective recomputation): only the input of the FFN module is kept.
  *   - Sec. 3.4 Eq. (2): G_W = G_y x^T ~= G_y (x^T V1) V1^T, V1 in R^{n x r}.
  *   - Sec. 2: LLaMA block, FFN = W_down( silu(W_gate u) * (W_up u) ), RMSNorm, residual.
+ * Around that hot path, further below: the standard-mode backward (Alg. 3, first branch), the
+ * block forward of both modes (Alg. 2), a stack of blocks in neighbor mode, tunable variants,
+ * the projection refresh (Alg. 3, every tau steps), Eq. (1) gradient averaging and AdamW (Alg. 1).
  *
  * Notation (row-major, token index along rows, weights in [out x in] layout):
  *   b tokens, d = d_model, f = d_ff, r = rank.
