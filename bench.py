@@ -255,7 +255,7 @@ def overhead(B, torch, desc, b, d, f, r, ldf, U, dY, Wg, Wu, Wd, projs, dU, dWg,
     stages = {k: round(ms / 5, 4) for k, (ms, n) in B.mecefo_profile_collect().items()}
     # attention core FLOPs with the causal half: five [S x S x dh] products per (sequence, head)
     core_flops = 5 * nb * heads * S * S * dh
-    core_ms = sum(stages.get(k, 0.0) for k in ("attn_probs", "attn_dv", "attn_ds", "attn_dq", "attn_dk"))
+    core_ms = sum(stages.get(k, 0.0) for k in ("attn_probs", "attn_dv", "attn_ds", "attn_dq", "attn_dk", "attn_fused_kv"))
     full_flops = 16 * b * d * f + 16 * b * d * d + core_flops
     return {
         "ffn_degraded_lowrank_ms": round(t_lr, 4),

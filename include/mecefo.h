@@ -315,7 +315,8 @@ typedef enum {
   MECEFO_STAGE_ROPE_BWD = 18,      /* inverse rotation of dQ, dK (and the angle tables)      */
   MECEFO_STAGE_QKV_WGRAD = 19,     /* dWq, dWk, dWv = (dQ, dK, dV)^T Xn                      */
   MECEFO_STAGE_QKV_DGRAD = 20,     /* dXn = dQ Wq + dK Wk + dV Wv                            */
-  MECEFO_STAGE_COUNT = 21
+  MECEFO_STAGE_ATTN_FUSED_KV = 21, /* dK, dV and dS in one kernel (P kept in registers)      */
+  MECEFO_STAGE_COUNT = 22
 } mecefo_stage_t;
 mecefo_status_t mecefo_profile_enable(int max_stage_launches);
 mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_stage);

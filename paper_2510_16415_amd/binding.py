@@ -321,7 +321,7 @@ def mecefo_projection_refresh(dtype, W, m, n, ldw, left, V0, ldv, r, power_iters
 
 STAGES = ["norm_fwd", "dgrad_down", "recompute", "swiglu_bwd", "dgrad_gate_up", "project", "contract",
           "splitk_reduce", "expand", "norm_bwd", "wgrad_exact", "attn_out_bwd", "attn_rowdot", "attn_probs",
-          "attn_dv", "attn_ds", "attn_dq", "attn_dk", "rope_bwd", "qkv_wgrad", "qkv_dgrad"]
+          "attn_dv", "attn_ds", "attn_dq", "attn_dk", "rope_bwd", "qkv_wgrad", "qkv_dgrad", "attn_fused_kv"]
 
 
 def mecefo_profile_enable(max_stage_launches: int):

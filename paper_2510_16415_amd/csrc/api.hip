@@ -2,6 +2,7 @@
 // order in which the kernels are enqueued.  Every arithmetic step runs in the kernels.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -779,32 +780,41 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
       STAGE(MECEFO_STAGE_ATTN_ROWDOT, s);
       HIP_TRY(launch_attn_rowdot(c.bf16, dO, dm, in->O, d.ld_act_d, D, c.b, S, a.heads, dh, s));
     }
-    {  // P = exp(scale Q K^T - L) below the diagonal, 0 above
-      STAGE(MECEFO_STAGE_ATTN_PROBS, s);
-      GemmLaunch g = new_launch(c, true, true, EPI_ATTN_P);
-      g.nprob = 1;
-      g.p[0] = prob(in->Q, nullptr, d.ld_act_d, in->K, nullptr, d.ld_act_d, P, nullptr, nullptr, w.ldp, S, S, dh, 1);
-      batched(g.p[0], tok_bo, tok_bi, tok_bo, tok_bi, sc_bo, sc_bi);
-      g.p[0].rowvec = in->L; g.p[0].scale = scale; g.p[0].causal = CAUSAL_TILE;
-      HIP_TRY(launch_gemm(g, s));
+    const char* attn_env = getenv("MECEFO_ATTN");     // "gemm" forces the five-product form
+    const bool fused = attn_bwd_fused_supported(c.bf16, dh, S, w.ldp) && !(attn_env && attn_env[0] == 'g');
+    if (fused) {  // dK, dV and dS in one kernel; P stays in registers
+      STAGE(MECEFO_STAGE_ATTN_FUSED_KV, s);
+      HIP_TRY(launch_attn_bwd_kv(in->Q, in->K, in->V, d.ld_act_d, dO, dK, dV, dm, in->L, D, P, w.ldp, a.batch, S,
+                                 a.heads, dh, scale, s));
     }
-    {  // dV = P^T dO   [seq x dh], contraction over the query index
-      STAGE(MECEFO_STAGE_ATTN_DV, s);
-      GemmLaunch g = new_launch(c, false, false, EPI_STORE);
-      g.nprob = 1;
-      g.p[0] = prob(P, nullptr, w.ldp, dO, nullptr, dm, dV, nullptr, nullptr, dm, S, dh, S, 1);
-      batched(g.p[0], sc_bo, sc_bi, ws_bo, ws_bi, ws_bo, ws_bi);
-      g.p[0].causal = CAUSAL_K_FROM_M;
-      HIP_TRY(launch_gemm(g, s));
-    }
-    {  // dS = P * (dO V^T - D) * scale, in place on P
-      STAGE(MECEFO_STAGE_ATTN_DS, s);
-      GemmLaunch g = new_launch(c, true, true, EPI_ATTN_DS);
-      g.nprob = 1;
-      g.p[0] = prob(dO, nullptr, dm, in->V, nullptr, d.ld_act_d, P, nullptr, nullptr, w.ldp, S, S, dh, 1);
-      batched(g.p[0], ws_bo, ws_bi, tok_bo, tok_bi, sc_bo, sc_bi);
-      g.p[0].rowvec = D; g.p[0].scale = scale; g.p[0].causal = CAUSAL_TILE;
-      HIP_TRY(launch_gemm(g, s));
+    if (!fused) {
+      {  // P = exp(scale Q K^T - L) below the diagonal, 0 above
+        STAGE(MECEFO_STAGE_ATTN_PROBS, s);
+        GemmLaunch g = new_launch(c, true, true, EPI_ATTN_P);
+        g.nprob = 1;
+        g.p[0] = prob(in->Q, nullptr, d.ld_act_d, in->K, nullptr, d.ld_act_d, P, nullptr, nullptr, w.ldp, S, S, dh, 1);
+        batched(g.p[0], tok_bo, tok_bi, tok_bo, tok_bi, sc_bo, sc_bi);
+        g.p[0].rowvec = in->L; g.p[0].scale = scale; g.p[0].causal = CAUSAL_TILE;
+        HIP_TRY(launch_gemm(g, s));
+      }
+      {  // dV = P^T dO   [seq x dh], contraction over the query index
+        STAGE(MECEFO_STAGE_ATTN_DV, s);
+        GemmLaunch g = new_launch(c, false, false, EPI_STORE);
+        g.nprob = 1;
+        g.p[0] = prob(P, nullptr, w.ldp, dO, nullptr, dm, dV, nullptr, nullptr, dm, S, dh, S, 1);
+        batched(g.p[0], sc_bo, sc_bi, ws_bo, ws_bi, ws_bo, ws_bi);
+        g.p[0].causal = CAUSAL_K_FROM_M;
+        HIP_TRY(launch_gemm(g, s));
+      }
+      {  // dS = P * (dO V^T - D) * scale, in place on P
+        STAGE(MECEFO_STAGE_ATTN_DS, s);
+        GemmLaunch g = new_launch(c, true, true, EPI_ATTN_DS);
+        g.nprob = 1;
+        g.p[0] = prob(dO, nullptr, dm, in->V, nullptr, d.ld_act_d, P, nullptr, nullptr, w.ldp, S, S, dh, 1);
+        batched(g.p[0], ws_bo, ws_bi, tok_bo, tok_bi, sc_bo, sc_bi);
+        g.p[0].rowvec = D; g.p[0].scale = scale; g.p[0].causal = CAUSAL_TILE;
+        HIP_TRY(launch_gemm(g, s));
+      }
     }
     {  // dQ = dS K   [seq x dh], contraction over the key index
       STAGE(MECEFO_STAGE_ATTN_DQ, s);
@@ -815,7 +825,7 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
       g.p[0].causal = CAUSAL_K_UPTO_M;
       HIP_TRY(launch_gemm(g, s));
     }
-    {  // dK = dS^T Q   [seq x dh], contraction over the query index
+    if (!fused) {  // dK = dS^T Q   [seq x dh], contraction over the query index
       STAGE(MECEFO_STAGE_ATTN_DK, s);
       GemmLaunch g = new_launch(c, false, false, EPI_STORE);
       g.nprob = 1;

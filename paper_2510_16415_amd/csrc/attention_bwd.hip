@@ -1,0 +1,275 @@
+// Fused causal attention backward for the key/value side (standard-mode block backward, Alg. 3
+// first branch): for one (sequence, head) and one block of 128 keys, a workgroup walks the query
+// blocks at and below the diagonal and keeps everything between the two softmax products and the
+// dK / dV accumulations in registers:
+//     S  = Q_i K_j^T          P  = exp(scale S - L_i)       (causal mask)
+//     dP = dO_i V_j^T         dS = P (dP - D_i) scale
+//     dV_j += P^T dO_i        dK_j += dS^T Q_i
+// Only dS goes to memory (bf16, [query x key] per product): dQ = dS K is then one batched GEMM on
+// the GEMM core.  The probabilities are never materialised.
+//
+// Mapping to v_mfma_f32_32x32x16_bf16 (wave64): each of the four waves owns 32 keys.  Its K_j and
+// V_j rows sit in registers as B operands for the whole walk.  S and dP come out with query rows
+// along the accumulator elements and the wave's keys along the lanes, which is exactly the A
+// operand of the two accumulations (keys along lanes, queries along K) once the K order of those
+// MFMAs is taken as the accumulator's own row order: a lane of the lower half-wave holds rows
+// 0-3 and 8-11 of every 16, the upper half rows 4-7 and 12-15, and the B operands (dO_i, Q_i, read
+// from LDS with transposing reads) are fetched in that same order.  No LDS round trip for P or dS.
+#include <math.h>
+
+#include "gemm_bf16_dtl.hip.h"
+#include "mecefo_internal.h"
+
+namespace mecefo {
+namespace {
+
+constexpr int kBr = 64;     // queries per step
+constexpr int kBc = 128;    // keys per workgroup (4 waves x 32)
+
+struct AttnBwdArgs {
+  const __bf16 *Q, *K, *V, *dO;     // token-major [tokens x ld*], head h at columns h*dh
+  int64_t ldq, ldk, ldv, lddo;
+  const float *L, *D;               // [nz][seq]
+  __bf16* dS;                       // [nz][seq x ldp]
+  int64_t ldp;
+  __bf16 *dK, *dV;                  // token-major, row stride ldg
+  int64_t ldg;
+  int seq, heads, nz, nkb;
+  float scale;
+};
+
+template <int DH> __device__ inline int tile_swz(int row) {
+  if constexpr (DH == 128) return row & 15;          // 16 chunks of 16 bytes per 256-byte row
+  else return (row >> 1) & 7;                        // 8 chunks per 128-byte row
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_kv_kernel(const AttnBwdArgs a) {
+  constexpr int RB = DH * 2;            // bytes per tile row
+  constexpr int CH = RB / 16;           // 16-byte chunks per row
+  constexpr int RPI = 64 / CH;          // tile rows per wave-wide fill instruction
+  constexpr int TILE = kBr * RB;        // one [64 x DH] tile
+  constexpr int FILLS = (kBr / RPI) / 4;   // fill instructions per wave and tile
+  constexpr int KT = DH / 16;           // MFMA K steps over the head dimension
+  constexpr int NB = DH / 32;           // 32-column blocks of dK / dV
+  constexpr float kLog2e = 1.44269504088896341f;
+  // LDS: two stages of (Q tile, dO tile), then L and D of the two stages
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];   // 4 * TILE + 4 * kBr * 4 bytes
+  float* ld_stage = (float*)(smem + 4 * TILE);     // [stage][0: L, 1: D][64]
+
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int hi = lane >> 5, l32 = lane & 31;
+  // heavy key blocks (small j: most query blocks below them) first
+  const int j = __builtin_amdgcn_readfirstlane((int)blockIdx.x / a.nz);
+  const int z = __builtin_amdgcn_readfirstlane((int)blockIdx.x - j * a.nz);
+  const int bi = z / a.heads, h = z - bi * a.heads;
+  const int seq = a.seq;
+  const int k0 = j * kBc;                              // first key of the workgroup
+  const int kw = k0 + 32 * wave;                       // first key of this wave
+  const int64_t tok0 = (int64_t)bi * seq;              // first token of the sequence
+  const __bf16* Qz = a.Q + tok0 * a.ldq + (int64_t)h * DH;
+  const __bf16* dOz = a.dO + tok0 * a.lddo + (int64_t)h * DH;
+  const float* Lz = a.L + (int64_t)z * seq;
+  const float* Dz = a.D + (int64_t)z * seq;
+  __bf16* dSz = a.dS + (int64_t)z * seq * a.ldp;
+
+  // K and V rows of this wave as B operands: lane holds key kw + l32, head-dim 16 t + 8 hi .. + 7
+  bf16x8_t kf[KT], vf[KT];
+  {
+    const int key = kw + l32;
+    const bool ok = key < seq;
+    const __bf16* kp = a.K + (tok0 + key) * a.ldk + (int64_t)h * DH + 8 * hi;
+    const __bf16* vp = a.V + (tok0 + key) * a.ldv + (int64_t)h * DH + 8 * hi;
+#pragma unroll
+    for (int s = 0; s < KT; ++s) {
+      bf16x8_t zero = {};
+      kf[s] = ok ? *(const bf16x8_t*)(kp + 16 * s) : zero;
+      vf[s] = ok ? *(const bf16x8_t*)(vp + 16 * s) : zero;
+    }
+  }
+
+  f32x16_t dk[NB], dv[NB];
+#pragma unroll
+  for (int n = 0; n < NB; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[n][e] = 0.f; dv[n][e] = 0.f; }
+
+  // Query blocks: the consumer of dS reads whole 256 x 256 blocks on the diagonal, so rows from the
+  // start of that block get zeros even where every query lies before the keys of this workgroup.
+  const int q_zero_from = (k0 >> 8) << 8;
+  const int qb_first = k0 / kBr;                       // first query block with a query >= k0
+  const int qb_end = (seq + kBr - 1) / kBr;
+
+  // zeros above the diagonal inside the diagonal block: rows [q_zero_from, k0), this wave's 32 keys
+  for (int q = q_zero_from + hi; q < k0 && q < seq; q += 2) {
+    const int key = kw + l32;
+    if (key < seq) dSz[(int64_t)q * a.ldp + key] = (__bf16)0.f;
+  }
+  const u32x4_t rq = make_rsrc_words(Qz);
+  const u32x4_t rdo = make_rsrc_words(dOz);
+  const uint32_t smem_addr = lds_address(smem);
+  // fill addressing: instruction f of this wave covers tile rows (4 f + wave) * RPI .. + RPI - 1
+  const int frow = lane / CH, fpc = lane % CH;
+  auto issue = [&](int qb, int stage) {
+    const int q0 = qb * kBr;
+    // L and D of the 64 queries first: the wait for these two loads must not cover the fills below
+    if (t < 2 * kBr) {
+      const int which = t >> 6, r = t & 63;
+      const int q = q0 + r;
+      float v = 0.f;
+      if (q < seq) v = which ? Dz[q] : Lz[q] * kLog2e;
+      ld_stage[(stage * 2 + which) * kBr + r] = v;
+    }
+#pragma unroll
+    for (int f = 0; f < FILLS; ++f) {
+      const int row = (f * 4 + wave) * RPI + frow;
+      const int c = fpc ^ tile_swz<DH>(row);
+      const bool ok = q0 + row < seq;
+      const uint32_t lds_off = (uint32_t)(stage * 2 * TILE + (f * 4 + wave) * 1024);
+      const uint32_t voq = ok ? (uint32_t)(((int64_t)(q0 + row) * a.ldq + c * 8) * 2) : kOOB;
+      const uint32_t vod = ok ? (uint32_t)(((int64_t)(q0 + row) * a.lddo + c * 8) * 2) : kOOB;
+      fill_lds_16B(rq, smem_addr + lds_off, voq, 0);
+      fill_lds_16B(rdo, smem_addr + lds_off + TILE, vod, 0);
+    }
+  };
+
+  // A-operand reads (rows = queries, K = head dim): row 32 mb + l32, chunk 2 s + hi
+  auto read_a = [&](const uint8_t* tile, int mb, int s) {
+    const int row = 32 * mb + l32;
+    const int c = (2 * s + hi) ^ tile_swz<DH>(row);
+    return *(const bf16x8_t*)(tile + row * RB + c * 16);
+  };
+  // B-operand reads for the accumulations (K = queries in accumulator order, N = head dim):
+  // 16 queries 16 u .., columns 32 n ..; two transposing reads of four query rows each
+  const int kq = (lane & 15) >> 2, b16 = (lane >> 4) & 1, q4 = lane & 3;
+  auto read_bt = [&](const uint8_t* tile, int u, int n) {
+    typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+    s16x4_t part[2];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int row = 16 * u + 4 * hi + 8 * hh + kq;
+      const int col = 32 * n + 16 * b16 + 4 * q4;                  // element column
+      const int c = (col >> 3) ^ tile_swz<DH>(row);
+      part[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + row * RB + c * 16 + (col & 4) * 2));
+    }
+    typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+    const s16x8_t v = __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, v);
+  };
+
+  const float c1 = a.scale * kLog2e;
+  if (qb_first < qb_end) {
+    issue(qb_first, 0);
+    for (int qb = qb_first; qb < qb_end; ++qb) {
+      const int stage = (qb - qb_first) & 1;
+      // wait for this stage's fills (issued one step ago), meet the other waves, prefetch the next
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (qb + 1 < qb_end) issue(qb + 1, stage ^ 1);
+      const uint8_t* tq = smem + stage * 2 * TILE;
+      const uint8_t* tdo = tq + TILE;
+      const float* Ls = ld_stage + (stage * 2) * kBr;
+      const float* Ds = Ls + kBr;
+      const int q0 = qb * kBr;
+
+      bf16x8_t pf[4], dsf[4];      // A operands of the accumulations: 16 queries each
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        f32x16_t s_acc, dp_acc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s_acc[e] = 0.f; dp_acc[e] = 0.f; }
+#pragma unroll
+        for (int s = 0; s < KT; ++s) {
+          s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a(tq, mb, s), kf[s], s_acc, 0, 0, 0);
+          dp_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a(tdo, mb, s), vf[s], dp_acc, 0, 0, 0);
+        }
+        const int key = kw + l32;
+        float p[16], ds[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int rbase = 32 * mb + 8 * g + 4 * hi;            // four consecutive query rows
+          const f32x4_t l4 = *(const f32x4_t*)(Ls + rbase);
+          const f32x4_t d4 = *(const f32x4_t*)(Ds + rbase);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int e = 4 * g + r;
+            const int q = q0 + rbase + r;
+            const bool live = key <= q && q < seq && key < seq;
+            const float pe = live ? __builtin_amdgcn_exp2f(s_acc[e] * c1 - l4[r]) : 0.f;
+            p[e] = pe;
+            ds[e] = pe * (dp_acc[e] - d4[r]) * a.scale;
+          }
+        }
+        // dS to memory: rows of 32 consecutive keys per half-wave
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int q = q0 + 32 * mb + 8 * (e >> 2) + 4 * hi + (e & 3);
+          if (q < seq && key < seq) dSz[(int64_t)q * a.ldp + key] = (__bf16)ds[e];
+        }
+#pragma unroll
+        for (int u2 = 0; u2 < 2; ++u2) {
+          bf16x8_t pv, dsv;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { pv[e] = (__bf16)p[8 * u2 + e]; dsv[e] = (__bf16)ds[8 * u2 + e]; }
+          pf[2 * mb + u2] = pv;
+          dsf[2 * mb + u2] = dsv;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+          dv[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[u], read_bt(tdo, u, n), dv[n], 0, 0, 0);
+          dk[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[u], read_bt(tq, u, n), dk[n], 0, 0, 0);
+        }
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  // dK, dV of this wave: accumulator rows are keys, lanes are head-dim columns
+#pragma unroll
+  for (int n = 0; n < NB; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int key = kw + 8 * (e >> 2) + 4 * hi + (e & 3);
+      if (key < seq) {
+        const int64_t off = (tok0 + key) * a.ldg + (int64_t)h * DH + 32 * n + l32;
+        a.dK[off] = (__bf16)dk[n][e];
+        a.dV[off] = (__bf16)dv[n][e];
+      }
+    }
+}
+
+}  // namespace
+
+bool attn_bwd_fused_supported(bool bf16, int dh, int seq, int64_t ldp) {
+  return bf16 && (dh == 64 || dh == 128) && seq >= 1 && ldp % 8 == 0;
+}
+
+// Q, K, V: caller tensors (row stride ld_in); dO, dK, dV: workspace tensors (row stride ld_ws).
+hipError_t launch_attn_bwd_kv(const void* Q, const void* K, const void* V, int64_t ld_in, const void* dO,
+                              void* dK, void* dV, int64_t ld_ws, const float* L, const float* D, void* dS,
+                              int64_t ldp, int batch, int seq, int heads, int dh, float scale, hipStream_t s) {
+  AttnBwdArgs a;
+  a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.V = (const __bf16*)V; a.dO = (const __bf16*)dO;
+  a.ldq = a.ldk = a.ldv = ld_in; a.lddo = ld_ws;
+  a.L = L; a.D = D; a.dS = (__bf16*)dS; a.ldp = ldp;
+  a.dK = (__bf16*)dK; a.dV = (__bf16*)dV; a.ldg = ld_ws;
+  a.seq = seq; a.heads = heads; a.nz = batch * heads; a.nkb = (seq + kBc - 1) / kBc;
+  a.scale = scale;
+  if (a.nz == 0 || seq == 0) return hipSuccess;
+  const dim3 grid((unsigned)(a.nz * a.nkb));
+  const int lds = 4 * kBr * dh * 2 + 4 * kBr * 4;
+  void (*kern)(const AttnBwdArgs) = dh == 128 ? attn_bwd_kv_kernel<128> : attn_bwd_kv_kernel<64>;
+  static bool attr_done[2] = {false, false};
+  if (!attr_done[dh == 128]) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done[dh == 128] = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace mecefo

@@ -104,4 +104,13 @@ hipError_t launch_softmax_rows(bool bf16, const float* S, int64_t lds, void* P, 
 hipError_t launch_attn_rowdot(bool bf16, const void* dO, int64_t lddo, const void* O, int64_t ldo, float* D,
                               int64_t tokens, int seq, int heads, int dh, hipStream_t s);
 
+
+// Fused causal attention backward for dK, dV (attention_bwd.hip): also writes dS = P (dP - D) scale
+// (bf16, [batch*heads][seq x ldp], zeros above the diagonal inside the diagonal 256-blocks) for the
+// batched dQ = dS K product that follows.  bf16, head dimension 64 or 128.
+bool attn_bwd_fused_supported(bool bf16, int dh, int seq, int64_t ldp);
+hipError_t launch_attn_bwd_kv(const void* Q, const void* K, const void* V, int64_t ld_in, const void* dO,
+                              void* dK, void* dV, int64_t ld_ws, const float* L, const float* D, void* dS,
+                              int64_t ldp, int batch, int seq, int heads, int dh, float scale, hipStream_t s);
+
 }  // namespace mecefo

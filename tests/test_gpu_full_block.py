@@ -125,6 +125,15 @@ def test_full_block_bf16_aligned_seq_large_tiles(monkeypatch):
     print(errs)
 
 
+@pytest.mark.parametrize("batch,seq,d,heads", [(2, 523, 256, 2), (1, 768, 256, 4), (2, 130, 128, 2)])
+def test_full_block_bf16_five_product_attention_path(batch, seq, d, heads, monkeypatch):
+    """Head dimensions 64 and 128 normally take the fused dK / dV kernel; MECEFO_ATTN=gemm keeps the
+    five batched products (the path every other head dimension and the fp32 configuration use)."""
+    monkeypatch.setenv("MECEFO_ATTN", "gemm")
+    _, _, errs = run_case(9, batch, seq, d, 344, heads, "bf16")
+    print(errs)
+
+
 def test_full_block_accumulate_alias_and_bf16_grads():
     p, X, dOut = make_case(5, 2, 96, 128, 344, 4, "bf16")
     want = O.block_bwd_full(X, dOut, p, 4, 2, 96, EPS)
