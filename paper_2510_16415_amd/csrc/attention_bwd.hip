@@ -17,6 +17,8 @@
 // from LDS with transposing reads) are fetched in that same order.  No LDS round trip for P or dS.
 #include <math.h>
 
+#include <type_traits>
+
 #include "gemm_bf16_dtl.hip.h"
 #include "mecefo_internal.h"
 
@@ -38,9 +40,14 @@ struct AttnBwdArgs {
   float scale;
 };
 
+// XOR swizzle of the 16-byte chunk index inside a tile row.  Two access patterns must stay free of
+// bank conflicts: 16 lanes reading one chunk column of 16 consecutive rows (A operands), and 32 lanes
+// reading 64 bytes of each of four consecutive rows (transposing B-operand reads).  The first needs
+// 16 distinct chunk positions over 16 rows, the second needs rows that differ in their low bits to land
+// in different 64-byte groups, hence the low row bits go to the high chunk bits.
 template <int DH> __device__ inline int tile_swz(int row) {
-  if constexpr (DH == 128) return row & 15;          // 16 chunks of 16 bytes per 256-byte row
-  else return (row >> 1) & 7;                        // 8 chunks per 128-byte row
+  if constexpr (DH == 128) return ((row & 3) << 2) | ((row >> 2) & 3);     // 16 chunks per 256-byte row
+  else return ((row >> 1) & 1) << 2 | ((row >> 2) & 1) << 1 | ((row >> 3) & 1);   // 8 chunks per 128-byte row
 }
 
 template <int DH>
@@ -111,119 +118,190 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(const AttnBwdArgs a) {
   const uint32_t smem_addr = lds_address(smem);
   // fill addressing: instruction f of this wave covers tile rows (4 f + wave) * RPI .. + RPI - 1
   const int frow = lane / CH, fpc = lane % CH;
+  // L (times log2 e) and D of a query block: threads 0-63 carry L, 64-127 carry D.  The values of the
+  // block after next are loaded into a register a whole step before they are written to LDS, so
+  // that no wave ever waits on these loads.
+  const int ld_which = t >> 6, ld_r = t & 63;
+  auto load_ld = [&](int qb) -> float {
+    float v = ld_which ? 0.f : INFINITY;      // rows behind the sequence: P = exp2(x - inf) = 0
+    const int q = qb * kBr + ld_r;
+    if (t < 2 * kBr && q < seq) v = ld_which ? Dz[q] : Lz[q] * kLog2e;
+    return v;
+  };
+  auto put_ld = [&](int stage, float v) {
+    if (t < 2 * kBr) ld_stage[(stage * 2 + ld_which) * kBr + ld_r] = v;
+  };
+  // per-lane parts of the fill offsets; the query block contributes a wave-uniform offset
+  uint32_t fq_off[FILLS], fd_off[FILLS];
+  int f_row[FILLS];
+#pragma unroll
+  for (int f = 0; f < FILLS; ++f) {
+    const int row = (f * 4 + wave) * RPI + frow;
+    const int c = fpc ^ tile_swz<DH>(row);
+    f_row[f] = row;
+    fq_off[f] = (uint32_t)(((int64_t)row * a.ldq + c * 8) * 2);
+    fd_off[f] = (uint32_t)(((int64_t)row * a.lddo + c * 8) * 2);
+  }
   auto issue = [&](int qb, int stage) {
     const int q0 = qb * kBr;
-    // L and D of the 64 queries first: the wait for these two loads must not cover the fills below
-    if (t < 2 * kBr) {
-      const int which = t >> 6, r = t & 63;
-      const int q = q0 + r;
-      float v = 0.f;
-      if (q < seq) v = which ? Dz[q] : Lz[q] * kLog2e;
-      ld_stage[(stage * 2 + which) * kBr + r] = v;
-    }
+    const uint32_t sq = (uint32_t)((int64_t)q0 * a.ldq * 2), sd = (uint32_t)((int64_t)q0 * a.lddo * 2);
 #pragma unroll
     for (int f = 0; f < FILLS; ++f) {
-      const int row = (f * 4 + wave) * RPI + frow;
-      const int c = fpc ^ tile_swz<DH>(row);
-      const bool ok = q0 + row < seq;
+      const bool ok = q0 + f_row[f] < seq;
       const uint32_t lds_off = (uint32_t)(stage * 2 * TILE + (f * 4 + wave) * 1024);
-      const uint32_t voq = ok ? (uint32_t)(((int64_t)(q0 + row) * a.ldq + c * 8) * 2) : kOOB;
-      const uint32_t vod = ok ? (uint32_t)(((int64_t)(q0 + row) * a.lddo + c * 8) * 2) : kOOB;
-      fill_lds_16B(rq, smem_addr + lds_off, voq, 0);
-      fill_lds_16B(rdo, smem_addr + lds_off + TILE, vod, 0);
+      fill_lds_16B(rq, smem_addr + lds_off, ok ? fq_off[f] : kOOB, sq);
+      fill_lds_16B(rdo, smem_addr + lds_off + TILE, ok ? fd_off[f] : kOOB, sd);
     }
   };
 
-  // A-operand reads (rows = queries, K = head dim): row 32 mb + l32, chunk 2 s + hi
-  auto read_a = [&](const uint8_t* tile, int mb, int s) {
+  // LDS read offsets, fixed for the whole walk.  A operands (rows = queries, K = head dim): row
+  // 32 mb + l32, chunk 2 s + hi; the K step only flips chunk bits, so it is an XOR with s << 5.
+  int a_off[2];
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb) {
     const int row = 32 * mb + l32;
-    const int c = (2 * s + hi) ^ tile_swz<DH>(row);
-    return *(const bf16x8_t*)(tile + row * RB + c * 16);
+    a_off[mb] = row * RB + ((hi ^ tile_swz<DH>(row)) << 4);
+  }
+  auto read_a = [&](const uint8_t* tile, int mb, int s) {
+    return *(const bf16x8_t*)(tile + (a_off[mb] ^ (s << 5)));
   };
-  // B-operand reads for the accumulations (K = queries in accumulator order, N = head dim):
-  // 16 queries 16 u .., columns 32 n ..; two transposing reads of four query rows each
+  // B operands of the accumulations (K = queries in accumulator order, N = head dim): 16 queries
+  // 16 u .., columns 32 n ..; two transposing reads of four query rows each.  The column block n
+  // flips chunk bits 2-3 (XOR with n << 6), the query group u is a constant row offset.
   const int kq = (lane & 15) >> 2, b16 = (lane >> 4) & 1, q4 = lane & 3;
+  int bt_off[2][NB];
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    const int row = 4 * hi + 8 * hh + kq;
+    const int base = row * RB + (((2 * b16 + (q4 >> 1)) ^ tile_swz<DH>(row)) << 4) + (q4 & 1) * 8;
+#pragma unroll
+    for (int n = 0; n < NB; ++n) bt_off[hh][n] = base ^ (n << 6);
+  }
   auto read_bt = [&](const uint8_t* tile, int u, int n) {
     typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
-    s16x4_t part[2];
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      const int row = 16 * u + 4 * hi + 8 * hh + kq;
-      const int col = 32 * n + 16 * b16 + 4 * q4;                  // element column
-      const int c = (col >> 3) ^ tile_swz<DH>(row);
-      part[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + row * RB + c * 16 + (col & 4) * 2));
-    }
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + bt_off[0][n] + u * 16 * RB));
+    const s16x4_t up = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + bt_off[1][n] + u * 16 * RB));
     typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-    const s16x8_t v = __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    const s16x8_t v = __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8_t, v);
   };
 
   const float c1 = a.scale * kLog2e;
+  const int key = kw + l32;
+  // dS fragments double as the values to store: fragment u holds, for this lane's key, the query rows
+  // 16 u + 4 hi + {0..3} and 16 u + 8 + 4 hi + {0..3}.  Stores are issued one step late, behind the next
+  // step's fills, so that the wait at the top of a step finds them long complete.
+  // One 2-byte buffer store per element: the row part of the offset is wave-uniform, and rows behind
+  // the sequence (or lanes whose key is) fall outside the descriptor's range and are dropped.
+  const __amdgpu_buffer_rsrc_t rds = __builtin_amdgcn_make_buffer_rsrc(dSz, 0, (int)((int64_t)seq * a.ldp * 2), 0x00020000);
+  const uint32_t ldp2 = (uint32_t)(a.ldp * 2);
+  const uint32_t ds_lane = key < seq ? (uint32_t)(key * 2) + (uint32_t)(4 * hi) * ldp2 : kOOB;
+  auto store_ds = [&](int q0, const bf16x8_t (&f)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const u32x4_t w = __builtin_bit_cast(u32x4_t, f[u]);       // two bf16 values per word
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t row = (uint32_t)(q0 + 16 * u + 8 * (e >> 2) + (e & 3));    // + 4 hi, in ds_lane
+        const uint32_t v = (e & 1) ? w[e >> 1] >> 16 : w[e >> 1];
+        __builtin_amdgcn_raw_buffer_store_b16((short)v, rds, ds_lane + row * ldp2, 0, 0);
+      }
+    }
+  };
+  bf16x8_t pf[4], dsf[4];        // A operands of the accumulations: 16 queries each
+  // One query block.  MASK: the block touches the diagonal or the end of the sequence (the only
+  // blocks that need the causal / length comparison per element).
+  auto step = [&](auto mask_tag, const uint8_t* tq, const uint8_t* tdo, const float* Ls, const float* Ds, int q0) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    f32x16_t s_acc[2], dp_acc[2];
+    auto sdp = [&](int mb) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s_acc[mb][e] = 0.f; dp_acc[mb][e] = 0.f; }
+      bf16x8_t qa[2], da[2];
+      qa[0] = read_a(tq, mb, 0); da[0] = read_a(tdo, mb, 0);
+#pragma unroll
+      for (int s = 0; s < KT; ++s) {
+        if (s + 1 < KT) { qa[(s + 1) & 1] = read_a(tq, mb, s + 1); da[(s + 1) & 1] = read_a(tdo, mb, s + 1); }
+        s_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s & 1], kf[s], s_acc[mb], 0, 0, 0);
+        dp_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[s & 1], vf[s], dp_acc[mb], 0, 0, 0);
+      }
+    };
+    auto softmax = [&](int mb) {
+      float p[16], ds[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int rbase = 32 * mb + 8 * g + 4 * hi;            // four consecutive query rows
+        const f32x4_t l4 = *(const f32x4_t*)(Ls + rbase);
+        const f32x4_t d4 = *(const f32x4_t*)(Ds + rbase);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int e = 4 * g + r;
+          float pe = __builtin_amdgcn_exp2f(s_acc[mb][e] * c1 - l4[r]);
+          if constexpr (MASK) {
+            const int q = q0 + rbase + r;
+            pe = (key <= q && key < seq) ? pe : 0.f;
+          }
+          p[e] = pe;
+          ds[e] = pe * (dp_acc[mb][e] - d4[r]) * a.scale;
+        }
+      }
+#pragma unroll
+      for (int u2 = 0; u2 < 2; ++u2) {
+        bf16x8_t pv, dsv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { pv[e] = (__bf16)p[8 * u2 + e]; dsv[e] = (__bf16)ds[8 * u2 + e]; }
+        pf[2 * mb + u2] = pv;
+        dsf[2 * mb + u2] = dsv;
+      }
+    };
+    bf16x8_t bo[2][NB], bq[2][NB];    // [slot][n]: dO^T and Q^T fragments
+    auto fetch_bt = [&](int slot, int u) {
+#pragma unroll
+      for (int n = 0; n < NB; ++n) { bo[slot][n] = read_bt(tdo, u, n); bq[slot][n] = read_bt(tq, u, n); }
+    };
+    auto acc = [&](int u) {
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        dv[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[u], bo[u & 1][n], dv[n], 0, 0, 0);
+        dk[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[u], bq[u & 1][n], dk[n], 0, 0, 0);
+      }
+    };
+    sdp(0);
+    sdp(1);
+    fetch_bt(0, 0);       // in flight while the softmax arithmetic runs
+    softmax(0);
+    softmax(1);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (u + 1 < 4) fetch_bt((u + 1) & 1, u + 1);
+      acc(u);
+    }
+  };
   if (qb_first < qb_end) {
+    put_ld(0, load_ld(qb_first));
+    float ld_next = load_ld(qb_first + 1);
     issue(qb_first, 0);
     for (int qb = qb_first; qb < qb_end; ++qb) {
       const int stage = (qb - qb_first) & 1;
       // wait for this stage's fills (issued one step ago), meet the other waves, prefetch the next
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      if (qb + 1 < qb_end) issue(qb + 1, stage ^ 1);
+      if (qb + 1 < qb_end) {
+        put_ld(stage ^ 1, ld_next);
+        issue(qb + 1, stage ^ 1);
+        ld_next = load_ld(qb + 2);
+      }
+      if (qb > qb_first) store_ds((qb - 1) * kBr, dsf);
       const uint8_t* tq = smem + stage * 2 * TILE;
       const uint8_t* tdo = tq + TILE;
       const float* Ls = ld_stage + (stage * 2) * kBr;
       const float* Ds = Ls + kBr;
       const int q0 = qb * kBr;
-
-      bf16x8_t pf[4], dsf[4];      // A operands of the accumulations: 16 queries each
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        f32x16_t s_acc, dp_acc;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s_acc[e] = 0.f; dp_acc[e] = 0.f; }
-#pragma unroll
-        for (int s = 0; s < KT; ++s) {
-          s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a(tq, mb, s), kf[s], s_acc, 0, 0, 0);
-          dp_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a(tdo, mb, s), vf[s], dp_acc, 0, 0, 0);
-        }
-        const int key = kw + l32;
-        float p[16], ds[16];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int rbase = 32 * mb + 8 * g + 4 * hi;            // four consecutive query rows
-          const f32x4_t l4 = *(const f32x4_t*)(Ls + rbase);
-          const f32x4_t d4 = *(const f32x4_t*)(Ds + rbase);
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int e = 4 * g + r;
-            const int q = q0 + rbase + r;
-            const bool live = key <= q && q < seq && key < seq;
-            const float pe = live ? __builtin_amdgcn_exp2f(s_acc[e] * c1 - l4[r]) : 0.f;
-            p[e] = pe;
-            ds[e] = pe * (dp_acc[e] - d4[r]) * a.scale;
-          }
-        }
-        // dS to memory: rows of 32 consecutive keys per half-wave
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int q = q0 + 32 * mb + 8 * (e >> 2) + 4 * hi + (e & 3);
-          if (q < seq && key < seq) dSz[(int64_t)q * a.ldp + key] = (__bf16)ds[e];
-        }
-#pragma unroll
-        for (int u2 = 0; u2 < 2; ++u2) {
-          bf16x8_t pv, dsv;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) { pv[e] = (__bf16)p[8 * u2 + e]; dsv[e] = (__bf16)ds[8 * u2 + e]; }
-          pf[2 * mb + u2] = pv;
-          dsf[2 * mb + u2] = dsv;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int n = 0; n < NB; ++n) {
-          dv[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[u], read_bt(tdo, u, n), dv[n], 0, 0, 0);
-          dk[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[u], read_bt(tq, u, n), dk[n], 0, 0, 0);
-        }
+      const bool need_mask = q0 < k0 + kBc || k0 + kBc > seq;
+      if (need_mask) step(std::true_type{}, tq, tdo, Ls, Ds, q0);
+      else step(std::false_type{}, tq, tdo, Ls, Ds, q0);
     }
+    store_ds((qb_end - 1) * kBr, dsf);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
