@@ -248,6 +248,14 @@ def overhead(B, torch, desc, b, d, f, r, ldf, U, dY, Wg, Wu, Wd, projs, dU, dWg,
         grads[k] = torch.zeros(d, d, device=dev)
     full = lambda: B.mecefo_block_bwd_full(desc, attn, inp, grads, 0, wsf)
     t_full = timed(full, 10)
+    # forward of the block in both modes (standard keeps Q, K, V, O, L, H; neighbor keeps H)
+    wsw = torch.empty(B.mecefo_block_fwd_workspace_bytes(desc, attn), dtype=torch.uint8, device=dev)
+    fin = {k: inp[k] for k in ("X", "g_attn", "g_ffn", "Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd")}
+    act = lambda: torch.empty(b, d, dtype=bf, device=dev)
+    fout = dict(Out=act(), H=act(), Q=act(), K=act(), V=act(), O=act(), L=torch.empty(nb * heads * S, device=dev))
+    t_fwd_std = timed(lambda: B.mecefo_block_fwd(desc, attn, fin, fout, wsw), 5)
+    t_fwd_nb = timed(lambda: B.mecefo_block_fwd(desc, attn, fin, dict(Out=fout["Out"], H=fout["H"]), wsw), 5)
+    del wsw, fout
     B.mecefo_profile_enable(32 * 5)
     for _ in range(5):
         full()
@@ -266,6 +274,8 @@ def overhead(B, torch, desc, b, d, f, r, ldf, U, dY, Wg, Wu, Wd, projs, dU, dWg,
         "block_full_ms": round(t_full, 4),
         "block_degraded_over_full": round(deg_block_ms / t_full, 4),
         "block_full_tflops": round(full_flops / (t_full * 1e-3) / 1e12, 1),
+        "block_fwd_standard_ms": round(t_fwd_std, 4),
+        "block_fwd_neighbor_ms": round(t_fwd_nb, 4),
         "attention_core_ms": round(core_ms, 4),
         "attention_core_tflops": round(core_flops / (core_ms * 1e-3) / 1e12, 1) if core_ms > 0 else None,
         "block_full_stages_ms": stages,
