@@ -164,6 +164,31 @@ int choose_splits(const Ctx& c, const int64_t c_rows[3], const int r[3]) {
   return s < 1 ? 1 : s;
 }
 
+// K splits for a launch that stores activation-dtype outputs but has too few 256 x 256 tiles to fill
+// the chip (mid-size layers: dU = dG Wg + dZ Wu with a small d, the projections with a small r):
+// the long contraction is cut so that about 256 workgroups exist, fp32 partials are summed in order.
+constexpr int kMaxStoreSplits = 4;
+int store_splits(bool bf16, int tiles_large, int min_stages) {
+  if (!bf16 || tiles_large <= 0 || tiles_large >= 128 || min_stages < 32) return 1;
+  int sp = cdiv(256, tiles_large);
+  if (sp > min_stages / 8) sp = min_stages / 8;
+  if (sp > kMaxStoreSplits) sp = kMaxStoreSplits;
+  return sp < 1 ? 1 : sp;
+}
+int store_splits_du(const Ctx& c) {   // dU [b x d], two K segments of length f
+  return store_splits(c.bf16, cdiv((int)c.b, 256) * cdiv(c.dm, 256), 2 * cdiv(c.ff, 64));
+}
+int store_splits_project(const Ctx& c, const int r[3], mecefo_side_t side) {   // T_i [b x r_i]
+  int tiles = 0, stages = 1 << 30;
+  for (int i = 0; i < 3; ++i) {
+    if (r[i] <= 0) continue;
+    tiles += cdiv((int)c.b, 256) * cdiv(r[i], 256);
+    const int k = side == MECEFO_SIDE_INPUT ? (i < 2 ? c.dm : c.ff) : (i < 2 ? c.ff : c.dm);
+    if (cdiv(k, 64) < stages) stages = cdiv(k, 64);
+  }
+  return tiles > 0 ? store_splits(c.bf16, tiles, stages) : 1;
+}
+
 Workspace layout(const Ctx& c, const int r[3], mecefo_side_t side, int force_splits) {
   Workspace w;
   size_t off = 0;
@@ -188,7 +213,16 @@ Workspace layout(const Ctx& c, const int r[3], mecefo_side_t side, int force_spl
     sum_c += c_rows[i] * rr;
   }
   w.splits = force_splits > 0 ? force_splits : choose_splits(c, c_rows, r);
-  w.partial = take(w.splits > 1 ? (size_t)w.splits * sum_c * 4 : 0);
+  // one partial buffer serves the launches that split K, one after the other on the stream
+  size_t partial = w.splits > 1 ? (size_t)w.splits * sum_c * 4 : 0;
+  const int sdu = store_splits_du(c), spr = store_splits_project(c, r, side);
+  if (sdu > 1 && (size_t)sdu * c.b * c.dm * 4 > partial) partial = (size_t)sdu * c.b * c.dm * 4;
+  if (spr > 1) {
+    size_t t = 0;
+    for (int i = 0; i < 3; ++i) t += (size_t)c.b * up(r[i] > 0 ? r[i] : 0, 8) * 4;
+    if ((size_t)spr * t > partial) partial = (size_t)spr * t;
+  }
+  w.partial = take(partial);
   w.dgp = take((size_t)rmsnorm_bwd_blocks(c.b) * c.dm * 4);
   w.total = off + 256;   // slack for aligning the caller's base pointer
   return w;
@@ -231,6 +265,30 @@ GemmProblem prob(const void* A0, const void* A1, int64_t lda, const void* B0, co
   return p;
 }
 
+// A store launch into the library's own buffers (row stride == ldc of every problem), cut along K
+// into `splits` parts when that fills the chip better.
+mecefo_status_t launch_store_split(const Ctx& c, const Bufs& bf, GemmLaunch& g, int splits, hipStream_t s) {
+  if (splits <= 1) {
+    HIP_TRY(launch_gemm(g, s));
+    return MECEFO_OK;
+  }
+  g.epi = EPI_SPLIT_F32;
+  g.splits = splits;
+  g.force_large = true;
+  g.partial = (float*)(bf.base + bf.w.partial);
+  void* C[3];
+  int64_t poff = 0;
+  for (int i = 0; i < g.nprob; ++i) {
+    C[i] = g.p[i].C[0];
+    g.partial_off[i] = poff;
+    poff += (int64_t)splits * g.p[i].M * g.p[i].ldc;
+  }
+  HIP_TRY(launch_gemm(g, s));
+  for (int i = 0; i < g.nprob; ++i)
+    HIP_TRY(launch_splitk_reduce(c.bf16, g.partial + g.partial_off[i], splits, (int64_t)g.p[i].M * g.p[i].ldc, C[i], s));
+  return MECEFO_OK;
+}
+
 // dA = dY Wd  ->  recompute G, Z from U and apply the SwiGLU backward in the epilogue
 // (DG = dG, DZ = dZ, AA = A)  ->  dU = dG Wg + dZ Wu.   Sec. 3.3 (Rcomp) + exact Dgrad.
 mecefo_status_t recompute_and_dgrad(const Ctx& c, const Bufs& bf, const void* U, int64_t ldu, const void* dY,
@@ -265,7 +323,8 @@ mecefo_status_t recompute_and_dgrad(const Ctx& c, const Bufs& bf, const void* U,
     g.nprob = 1;
     g.p[0] = prob(DG, DZ, c.ldf, Wg, Wu, d.ld_w_fd, dU, nullptr, nullptr, lddu, b, c.dm, c.ff, 2);
     g.p[0].kpad_ok = 1;   // DG / DZ padding columns were written as zeros; the weight rows are predicated exactly
-    HIP_TRY(launch_gemm(g, s));
+    // K is only cut when dU is the workspace's own [b x d] buffer (the reduction writes whole rows)
+    TRY(launch_store_split(c, bf, g, dU == base + bf.w.dU ? store_splits_du(c) : 1, s));
   }
   return MECEFO_OK;
 }
@@ -324,7 +383,9 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
       const void* a_op = in ? X[i] : Gy[i];
       g.p[j].kpad_ok = (a_op == base + bf.w.AA || a_op == base + bf.w.DG || a_op == base + bf.w.DZ) ? 1 : 0;
     }
-    HIP_TRY(launch_gemm(g, s));
+    int rr[3] = {0, 0, 0};
+    for (int j = 0; j < n_lr; ++j) rr[lr[j]] = P[lr[j]].r;
+    TRY(launch_store_split(c, bf, g, store_splits_project(c, rr, side), s));
   }
   {  // contract over tokens: C = (Gy or X)^T T   [rows x r], K = b
     const int splits = b > 0 ? bf.w.splits : 1;
