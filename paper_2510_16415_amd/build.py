@@ -17,7 +17,7 @@ LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libmecefo.so")
 OBJDIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["api.hip", "elementwise.hip", "attention.hip", "attention_bwd.hip", "projection.hip", "optimizer.hip", "gemm_f32.hip", "gemm_bf16_nt.hip", "gemm_bf16_nn.hip",
+SOURCES = ["api.hip", "elementwise.hip", "attention.hip", "attention_bwd.hip", "attention_fwd.hip", "projection.hip", "optimizer.hip", "gemm_f32.hip", "gemm_bf16_nt.hip", "gemm_bf16_nn.hip",
            "gemm_bf16_tn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

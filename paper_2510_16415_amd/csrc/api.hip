@@ -992,7 +992,10 @@ mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_att
   HIP_TRY(launch_rope(c.bf16, Q, ldq, cs, sn, c.b, S, a.heads, dh, false, s));
   HIP_TRY(launch_rope(c.bf16, K, ldq, cs, sn, c.b, S, a.heads, dh, false, s));
   const float scale = 1.0f / sqrtf((float)dh);
-  for (int bi = 0; bi < a.batch; ++bi)
+  const char* attn_env = getenv("MECEFO_ATTN");     // "gemm" forces the materialised-score form
+  const bool fused = !(attn_env && attn_env[0] == 'g') && attn_fwd_fused_supported(c.bf16, dh, S, ldq);
+  if (fused) HIP_TRY(launch_attn_fwd(Q, K, V, O, ldq, L, a.batch, S, a.heads, dh, scale, s));
+  for (int bi = 0; bi < (fused ? 0 : a.batch); ++bi)
     for (int h0 = 0; h0 < a.heads; h0 += w.hc) {
       const int hc = a.heads - h0 < w.hc ? a.heads - h0 : w.hc;
       const int64_t tok = ((int64_t)bi * S * ldq + (int64_t)h0 * dh) * c.esz;

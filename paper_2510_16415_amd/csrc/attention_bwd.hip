@@ -19,7 +19,7 @@
 
 #include <type_traits>
 
-#include "gemm_bf16_dtl.hip.h"
+#include "attention_tiles.hip.h"
 #include "mecefo_internal.h"
 
 namespace mecefo {
@@ -39,16 +39,6 @@ struct AttnBwdArgs {
   int seq, heads, nz, nkb;
   float scale;
 };
-
-// XOR swizzle of the 16-byte chunk index inside a tile row.  Two access patterns must stay free of
-// bank conflicts: 16 lanes reading one chunk column of 16 consecutive rows (A operands), and 32 lanes
-// reading 64 bytes of each of four consecutive rows (transposing B-operand reads).  The first needs
-// 16 distinct chunk positions over 16 rows, the second needs rows that differ in their low bits to land
-// in different 64-byte groups, hence the low row bits go to the high chunk bits.
-template <int DH> __device__ inline int tile_swz(int row) {
-  if constexpr (DH == 128) return ((row & 3) << 2) | ((row >> 2) & 3);     // 16 chunks per 256-byte row
-  else return ((row >> 1) & 1) << 2 | ((row >> 2) & 1) << 1 | ((row >> 3) & 1);   // 8 chunks per 128-byte row
-}
 
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(const AttnBwdArgs a) {

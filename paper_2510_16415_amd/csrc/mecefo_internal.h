@@ -113,4 +113,12 @@ hipError_t launch_attn_bwd_kv(const void* Q, const void* K, const void* V, int64
                               void* dK, void* dV, int64_t ld_ws, const float* L, const float* D, void* dS,
                               int64_t ldp, int batch, int seq, int heads, int dh, float scale, hipStream_t s);
 
+
+// Fused causal attention forward: O = softmax(scale Q K^T) V and the row log-sum-exp L [batch*heads][seq],
+// no score or probability buffer.  Q, K, V, O token-major with row stride ld (elements), head h at
+// columns h*dh.  bf16, head dimension 64 or 128, ld a multiple of 8.
+bool attn_fwd_fused_supported(bool bf16, int dh, int seq, int64_t ld);
+hipError_t launch_attn_fwd(const void* Q, const void* K, const void* V, void* O, int64_t ld, float* L, int batch,
+                           int seq, int heads, int dh, float scale, hipStream_t s);
+
 }  // namespace mecefo

@@ -67,6 +67,22 @@ def test_block_fwd_bf16_forced_tiles_cross_the_diagonal(tile, monkeypatch):
     print(tile, run_fwd(24, 1, 768, 256, 344, 4, "bf16")[-1])
 
 
+@pytest.mark.parametrize("batch,seq,d,heads,pad", [(2, 523, 256, 2, 0), (1, 768, 256, 4, 8), (3, 1, 128, 2, 0),
+                                                   (2, 63, 128, 1, 0), (1, 129, 64, 1, 8), (2, 257, 512, 4, 0)])
+def test_block_fwd_bf16_fused_attention_shapes(batch, seq, d, heads, pad):
+    """Head dimensions 64 and 128 take the fused attention forward: single tokens, sequences shorter
+    than one key block, one past a block boundary, padded row strides."""
+    print(run_fwd(29, batch, seq, d, 200, heads, "bf16", pad=pad)[-1])
+
+
+@pytest.mark.parametrize("batch,seq,d,heads", [(2, 523, 256, 2), (1, 768, 256, 4)])
+def test_block_fwd_bf16_materialised_scores_path(batch, seq, d, heads, monkeypatch):
+    """MECEFO_ATTN=gemm keeps the chunked fp32-score form (the one other head dimensions use) covered
+    at head dimensions 128 and 64."""
+    monkeypatch.setenv("MECEFO_ATTN", "gemm")
+    print(run_fwd(30, batch, seq, d, 344, heads, "bf16")[-1])
+
+
 def test_neighbor_mode_forward_keeps_only_h_and_matches_standard_mode():
     p, X, dOut, blk, fwd, std, want, _ = run_fwd(25, 2, 200, 128, 344, 4, "bf16")
     nb = fwd.run(neighbor=True)
