@@ -189,6 +189,11 @@ typedef struct {
   float* L;              /* given iff Q is given */
 } mecefo_block_fwd_outputs_t;
 
+/* Workspace: a few [b x d] activations and one [b x ld_act_f] activation.  bf16 with head dimension
+ * 64 or 128 runs the attention as one fused kernel (running maximum and sum per query, no score
+ * buffer); other shapes add fp32 scores and probabilities of a chunk of heads (at most 256 MiB of
+ * scores).  The environment variable MECEFO_ATTN=gemm selects the second form everywhere (testing);
+ * it is read by the query and by the call, so set it before both. */
 mecefo_status_t mecefo_block_fwd_workspace_bytes(const mecefo_ffn_desc_t* desc,
     const mecefo_attn_desc_t* attn, size_t* out_bytes);
 mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,

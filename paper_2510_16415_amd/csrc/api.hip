@@ -494,6 +494,16 @@ struct FwdWs {
   int hc;        // heads per attention chunk
 };
 
+// The block forward takes the fused attention kernel (no score or probability buffer) whenever it is
+// built for the shape; MECEFO_ATTN=gemm keeps the materialised-score form for testing.  The
+// workspace query and the call consult the same predicate.
+bool fwd_attention_fused(const Ctx& c, const mecefo_attn_desc_t& a) {
+  const char* env = getenv("MECEFO_ATTN");
+  if (env && env[0] == 'g') return false;
+  // bf16 descriptors have row strides that are multiples of 8 (checked with the descriptor)
+  return attn_fwd_fused_supported(c.bf16, c.dm / (a.heads > 0 ? a.heads : 1), a.seq > 0 ? a.seq : 1, 8);
+}
+
 FwdWs fwd_layout(const Ctx& c, const mecefo_attn_desc_t& a) {
   FwdWs w;
   size_t off = 0;
@@ -512,8 +522,9 @@ FwdWs fwd_layout(const Ctx& c, const mecefo_attn_desc_t& a) {
   if (hc < 1) hc = 1;
   if (hc > a.heads) hc = a.heads;
   w.hc = (int)hc;
-  w.S32 = take((size_t)hc * per_head);
-  w.P = take((size_t)hc * a.seq * w.ldp * c.esz);
+  const bool fused = fwd_attention_fused(c, a);
+  w.S32 = take(fused ? 0 : (size_t)hc * per_head);
+  w.P = take(fused ? 0 : (size_t)hc * a.seq * w.ldp * c.esz);
   w.cs = take((size_t)a.seq * (dh / 2) * 4);
   w.sn = take((size_t)a.seq * (dh / 2) * 4);
   w.total = off + 256;
@@ -992,8 +1003,7 @@ mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_att
   HIP_TRY(launch_rope(c.bf16, Q, ldq, cs, sn, c.b, S, a.heads, dh, false, s));
   HIP_TRY(launch_rope(c.bf16, K, ldq, cs, sn, c.b, S, a.heads, dh, false, s));
   const float scale = 1.0f / sqrtf((float)dh);
-  const char* attn_env = getenv("MECEFO_ATTN");     // "gemm" forces the materialised-score form
-  const bool fused = !(attn_env && attn_env[0] == 'g') && attn_fwd_fused_supported(c.bf16, dh, S, ldq);
+  const bool fused = fwd_attention_fused(c, a);
   if (fused) HIP_TRY(launch_attn_fwd(Q, K, V, O, ldq, L, a.batch, S, a.heads, dh, scale, s));
   for (int bi = 0; bi < (fused ? 0 : a.batch); ++bi)
     for (int h0 = 0; h0 < a.heads; h0 += w.hc) {

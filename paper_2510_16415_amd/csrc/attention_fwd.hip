@@ -33,7 +33,7 @@ struct AttnFwdArgs {
 };
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnFwdArgs a) {
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const AttnFwdArgs a) {
   constexpr int RB = DH * 2, CH = RB / 16, RPI = 64 / CH, TILE = kFk * RB;
   constexpr int FILLS = (kFk / RPI) / 4;
   constexpr int KT = DH / 16, NB = DH / 32;
