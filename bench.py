@@ -128,6 +128,14 @@ def main():
     t1 = time.perf_counter()
     stages = B.mecefo_profile_collect()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # per-step spread (outside the timed region): one event pair per step on the launch stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in ev:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in ev) or [ms_per_step]
     tokens_per_s = b / (ms_per_step * 1e-3)
 
     flops_layer = b * (10 * d * f + 6 * r * (d + f)) + 6 * r * d * f
@@ -167,6 +175,8 @@ def main():
                                "bf16 storage / fp32 accumulate, SIDE_INPUT projections"
                    if cfg.name == "C5" else f"{cfg.name}: one layer d={d} f={f} tokens={b} r={r}",
                    "tokens": b, "d_model": d, "d_ff": f, "rank": r},
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4),
+        "ms_per_step_min": round(per_step[0], 4),
         "tflops_per_layer": round(flops_layer / (ms_per_step * 1e-3) / 1e12, 1),
         "frac_of_bf16_mfma_peak": round(flops_layer / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "algorithmic_flops_per_layer": flops_layer,
@@ -188,6 +198,7 @@ def main():
         out["variants"] = variants(B, torch, desc, b, d, f, r, ldf, H, dOut, gamma, Wg, Wu, Wd, (Pg, Pu, Pd), dX,
                                    dgamma, dWg, dWu, dWd)
         out["neighbor_stack"] = neighbor_stack(B, torch, I)
+        out["step_compositions_per_layer"] = step_compositions(B, torch, I)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
@@ -427,6 +438,76 @@ def neighbor_stack(B, torch, I, name="C2"):
             "standard_mode_with_saved_G_Z": kept_standard + 2 * b * ldf * 2,
         },
     }
+
+
+def step_compositions(B, torch, I, names=("C3", "C4")):
+    """Per-layer backward time of one node's step in the three compositions the method implies:
+    healthy (one standard-mode backward), neighbor as in Alg. 3 (own and absorbed micro-batch both in
+    neighbor mode; the second accumulates), and neighbor with only the absorbed micro-batch degraded
+    (standard-mode backward of the own one + a degraded one accumulating into the same buffers)."""
+    dev = torch.device("cuda:0")
+    bf = torch.bfloat16
+    out = {}
+    for name in names:
+        cfg = I.CONFIGS[name]
+        b, d, f, r = cfg.tokens, cfg.d_model, cfg.d_ff, cfg.rank
+        ldf = (f + 7) // 8 * 8
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4242 + cfg.index)
+
+        def rn(rows, cols, std=1.0, ld=None):
+            t = torch.zeros(rows, ld or cols, dtype=bf, device=dev)
+            t[:, :cols] = (torch.randn(rows, cols, generator=gen, device=dev) * std).to(bf)
+            return t
+
+        desc = B.make_desc(b, d, f, B.BF16, B.F32, d, ldf, d, ldf)
+        attn = B.make_attn_desc(cfg.batch, cfg.seq, cfg.heads, d)
+        ones = lambda: torch.ones(d, dtype=bf, device=dev)
+        inp = dict(X=rn(b, d), H=rn(b, d), dOut=rn(b, d), g_attn=ones(), g_ffn=ones(),
+                   Wg=rn(f, d, 0.02), Wu=rn(f, d, 0.02), Wd=rn(d, f, 0.02, ldf),
+                   Q=rn(b, d), K=rn(b, d), V=rn(b, d), O=rn(b, d, 0.1))
+        for k in ("Wq", "Wk", "Wv", "Wo"):
+            inp[k] = rn(d, d, 0.02)
+        # timing only: a constant log-sum-exp keeps every probability finite and below one
+        inp["L"] = torch.full((cfg.batch * cfg.heads * cfg.seq,), 30.0, device=dev)
+        Ps = [rn(d, r, d ** -0.5), rn(d, r, d ** -0.5), rn(f, r, f ** -0.5)]
+        projs = [B.proj(P, r) for P in Ps]
+        grads = dict(dX=torch.empty(b, d, dtype=bf, device=dev), dg_attn=torch.zeros(d, device=dev),
+                     dg_ffn=torch.zeros(d, device=dev), dWg=torch.zeros(f, d, device=dev),
+                     dWu=torch.zeros(f, d, device=dev), dWd=torch.zeros(d, ldf, device=dev))
+        for k in ("dWq", "dWk", "dWv", "dWo"):
+            grads[k] = torch.zeros(d, d, device=dev)
+        ws = torch.empty(max(B.mecefo_block_full_workspace_bytes(desc, attn), B.mecefo_workspace_bytes(desc, r, r, r)),
+                         dtype=torch.uint8, device=dev)
+
+        def full(acc):
+            B.mecefo_block_bwd_full(desc, attn, inp, grads, acc, ws)
+
+        def skip(acc):
+            B.mecefo_block_bwd_skip(desc, inp["H"], inp["dOut"], inp["g_ffn"], inp["Wg"], inp["Wu"], inp["Wd"], *projs,
+                                    B.SIDE_INPUT, grads["dX"], grads["dg_ffn"], grads["dWg"], grads["dWu"], grads["dWd"],
+                                    acc, ws)
+
+        def timed(fn, n=20):
+            fn()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) * 1e3 / n
+
+        t_h = timed(lambda: full(0))
+        t_n = timed(lambda: (skip(0), skip(1)))
+        t_m = timed(lambda: (full(0), skip(1)))
+        out[name] = {
+            "layer": f"tokens={b} per micro-batch, d={d}, f={f}, heads={cfg.heads}, seq={cfg.seq}, r={r}",
+            "healthy_one_standard_bwd_ms": round(t_h, 4),
+            "neighbor_two_degraded_bwd_ms": round(t_n, 4),
+            "neighbor_standard_plus_degraded_bwd_ms": round(t_m, 4),
+            "neighbor_over_healthy": round(t_n / t_h, 3),
+        }
+    return out
 
 
 def cpu_baseline(cfg):
