@@ -330,12 +330,9 @@ hipError_t launch_attn_bwd_kv(const void* Q, const void* K, const void* V, int64
   const dim3 grid((unsigned)(a.nz * a.nkb));
   const int lds = 4 * kBr * dh * 2 + 4 * kBr * 4;
   void (*kern)(const AttnBwdArgs) = dh == 128 ? attn_bwd_kv_kernel<128> : attn_bwd_kv_kernel<64>;
-  static bool attr_done[2] = {false, false};
-  if (!attr_done[dh == 128]) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done[dh == 128] = true;
-  }
+  static LdsLimitOnce limit[2];
+  const hipError_t e = limit[dh == 128].ensure((const void*)kern, lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a);
   return hipGetLastError();
 }

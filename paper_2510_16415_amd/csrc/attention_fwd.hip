@@ -232,12 +232,9 @@ hipError_t launch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
   if (a.nz == 0 || seq == 0) return hipSuccess;
   const int lds = 4 * kFk * dh * 2;
   void (*kern)(const AttnFwdArgs) = dh == 128 ? attn_fwd_kernel<128> : attn_fwd_kernel<64>;
-  static bool attr_done[2] = {false, false};
-  if (!attr_done[dh == 128]) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done[dh == 128] = true;
-  }
+  static LdsLimitOnce limit[2];
+  const hipError_t e = limit[dh == 128].ensure((const void*)kern, lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.nz * a.nqb)), dim3(256), lds, s, a);
   return hipGetLastError();
 }

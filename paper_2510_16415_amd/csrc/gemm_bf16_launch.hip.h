@@ -79,12 +79,9 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
   void (*kern)(const KArgs);
   if constexpr (DTL) kern = gemm_bf16_dtl_kernel<Cfg, Pipe, AKC, BKC, EPI>;
   else kern = gemm_bf16_kernel<Cfg, AKC, BKC, EPI>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimitOnce limit;      // one per template instantiation, i.e. per kernel
+  const hipError_t e = limit.ensure((const void*)kern, LDS);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(tiles * a.splits), dim3(Cfg::NT), LDS, stream, a);
   return hipGetLastError();
 }

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace mecefo {
 
 enum Epilogue : int {
@@ -64,6 +66,23 @@ struct GemmLaunch {
 
 // Records the thread-local error text returned by mecefo_last_error() and returns `status`.
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// Kernels that need more than 64 KiB of dynamic LDS must have the limit raised once per device (the
+// attribute belongs to the kernel's code object on that device).  One instance per kernel; ensure()
+// is cheap after the first call on a device and safe from several host threads.
+struct LdsLimitOnce {
+  std::atomic<uint64_t> done{0};      // bit i: raised on device i (devices above 63 set it every time)
+  hipError_t ensure(const void* kern, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+  }
+};
 
 // Returns hipSuccess or the launch error.  Only enqueues.
 hipError_t launch_gemm(GemmLaunch& g, hipStream_t stream);
