@@ -56,6 +56,22 @@ def test_block_bwd_skip_ragged(shape, dtype):
     assert_close(got, oracle_block(c), TOL[dtype], label=f"{shape} {dtype}: ")
 
 
+@pytest.mark.parametrize("alias", [False, True])
+@pytest.mark.parametrize("d", [1024, 1032, 2056, 4104, 8192, 8200])
+def test_norm_kernels_over_row_lengths(d, alias):
+    """The norm recompute and the fused norm backward / residual / gain-gradient pass pick a kernel by
+    row length (a wave per row, the workgroup per row with 1, 2 or 4 vectors per thread, and the
+    two-pass form above 8192 columns); 37 rows leave a ragged last block of rows.  dX aliasing dOut
+    must give the same result."""
+    b, f, r = 37, 24, 5
+    c = make_case(700 + d, b, d, f, r, "bf16")
+    lay = Layer(b, d, f, "bf16", c["Wg"], c["Wu"], c["Wd"], c["gamma"], c["Pg"], c["Pu"], c["Pd"], EPS)
+    got = lay.block_bwd_skip(c["H"], c["dOut"], alias=alias)
+    assert_close(got, oracle_block(c), TOL["bf16"], label=f"d={d} alias={alias}: ")
+    no_dgamma = lay.block_bwd_skip(c["H"], c["dOut"], want_dgamma=False)
+    assert np.array_equal(no_dgamma["dX"], got["dX"])
+
+
 @pytest.mark.parametrize("tile", ["S", "L4", "L8R", "L8"])
 @pytest.mark.parametrize("shape", [(300, 264, 333, 40), (513, 512, 1000, 129), (700, 520, 1365, 264)])
 def test_every_tile_configuration_on_ragged_shapes(shape, tile, monkeypatch):
