@@ -150,13 +150,13 @@ def main():
     gemm_stages = {k: v for k, v in stage_report.items() if "tflops" in v}
     dom = max(gemm_stages, key=lambda k: gemm_stages[k]["ms"])
     dom_tflops = sf[dom] / (gemm_stages[dom]["ms"] * 1e-3) / 1e12
-    # HBM-bound kernels: algorithmic bytes (bf16): norm recompute 2 b d, norm backward + residual 4 b d
-    # (+ the gain-gradient pass re-reading dU and H: 2 b d)
+    # HBM-bound kernels: algorithmic bytes (bf16): norm recompute 2 b d; norm backward + residual +
+    # gain-gradient partials in one pass 4 b d (dU, H, dOut in; dX out)
     hbm = {}
     if "norm_fwd" in stage_report:
         hbm["norm_fwd_GBs"] = round(2 * b * d * 2 / (stage_report["norm_fwd"]["ms"] * 1e-3) / 1e9, 1)
     if "norm_bwd" in stage_report:
-        hbm["norm_bwd_GBs"] = round(6 * b * d * 2 / (stage_report["norm_bwd"]["ms"] * 1e-3) / 1e9, 1)
+        hbm["norm_bwd_GBs"] = round(4 * b * d * 2 / (stage_report["norm_bwd"]["ms"] * 1e-3) / 1e9, 1)
 
     out = {
         "metric": "degraded-block bwd tokens/sec",
