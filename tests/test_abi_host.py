@@ -160,3 +160,34 @@ def test_block_fwd_validation():
     tin.Wo = None
     st = lib.mecefo_block_fwd(C.byref(d), C.byref(a), C.byref(tin), C.byref(tout), ws, 1 << 30, None)
     assert st == B.ERR_INVALID_ARG and "Wo is NULL" in B.mecefo_last_error()
+
+
+def test_stage_names_follow_the_header_enum():
+    hdr = open(os.path.join(ROOT, "include", "mecefo.h")).read()
+    enum = re.findall(r"MECEFO_STAGE_([A-Z_]+)\s*=\s*(\d+)", hdr)
+    count = dict(enum).pop("COUNT")
+    names = [n.lower() for n, v in sorted(((n, int(v)) for n, v in enum if n != "COUNT"), key=lambda x: x[1])]
+    assert names == B.STAGES and int(count) == len(B.STAGES)
+
+
+def test_forward_workspace_has_no_score_buffer_when_the_attention_is_fused(monkeypatch):
+    """bf16 with head dimension 64 or 128 runs the fused attention forward: the workspace is a handful
+    of activations.  MECEFO_ATTN=gemm (or another head dimension) adds fp32 scores and probabilities."""
+    b, d, f, seq, batch = 8192, 4096, 11008, 2048, 4
+    desc = B.make_desc(b, d, f, B.BF16)
+    monkeypatch.delenv("MECEFO_ATTN", raising=False)
+    fused = B.mecefo_block_fwd_workspace_bytes(desc, B.make_attn_desc(batch, seq, 32, d))       # dh = 128
+    other = B.mecefo_block_fwd_workspace_bytes(desc, B.make_attn_desc(batch, seq, 16, d))       # dh = 256
+    monkeypatch.setenv("MECEFO_ATTN", "gemm")
+    forced = B.mecefo_block_fwd_workspace_bytes(desc, B.make_attn_desc(batch, seq, 32, d))
+    act = b * d * 2
+    assert 6 * act <= fused <= 6 * act + b * f * 2 + (16 << 20)
+    assert forced >= fused + (256 << 20) and other >= fused + (128 << 20)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
