@@ -711,21 +711,29 @@ mecefo_status_t mecefo_block_bwd_skip_ex(const mecefo_ffn_desc_t* desc, const vo
   }
   void* dUb = base + bf.w.dU;
   TRY(recompute_and_dgrad(c, bf, U, ldu, dOut, desc->ld_act_d, Wg, Wu, Wd, Gs, Zs, dUb, c.dm, s));
-  // Eq. (2) reads dOut (as the down projection's output gradient), so it runs before dX may overwrite dOut.
+  // Skip the MHA connection: the gradient handed to the previous layer is dH = dOut + normbwd(dU).
+  auto norm_backward = [&]() -> mecefo_status_t {
+    STAGE(MECEFO_STAGE_NORM_BWD, s);
+    if (gamma) {
+      const int nblk = rmsnorm_bwd_blocks(c.b);
+      float* dgp = dgamma ? (float*)(base + bf.w.dgp) : nullptr;
+      if (c.b > 0)
+        HIP_TRY(launch_rmsnorm_bwd(c.bf16, dUb, c.dm, H, desc->ld_act_d, rstd, gamma, dOut, desc->ld_act_d, dX,
+                                   desc->ld_act_d, dgp, nblk, c.b, c.dm, s));
+      if (dgamma) HIP_TRY(launch_dgamma_reduce(dgp, c.b > 0 ? nblk : 0, c.dm, dgamma, c.grad_f32, c.bf16, accumulate, s));
+    } else if (c.b > 0) {
+      HIP_TRY(launch_add(c.bf16, dOut, desc->ld_act_d, dUb, c.dm, dX, desc->ld_act_d, c.b, c.dm, s));
+    }
+    return MECEFO_OK;
+  };
+  // Eq. (2) reads dOut (the down projection's output gradient) and, without a norm, H itself: when dX
+  // is a buffer of its own the norm backward goes first, while dU is still in the caches and before
+  // the weight gradients flood them; when dX overwrites dOut (or H) it has to wait for Eq. (2).
+  const bool dx_first = dX != dOut && dX != H;
+  if (dx_first) TRY(norm_backward());
   void* dW[3] = {dWg, dWu, dWd};
   TRY(lowrank_wgrad(c, bf, U, ldu, dOut, desc->ld_act_d, P, side, dW, accumulate, s, exact_mask));
-  // Skip the MHA connection: the gradient handed to the previous layer is dH = dOut + normbwd(dU).
-  STAGE(MECEFO_STAGE_NORM_BWD, s);
-  if (gamma) {
-    const int nblk = rmsnorm_bwd_blocks(c.b);
-    float* dgp = dgamma ? (float*)(base + bf.w.dgp) : nullptr;
-    if (c.b > 0)
-      HIP_TRY(launch_rmsnorm_bwd(c.bf16, dUb, c.dm, H, desc->ld_act_d, rstd, gamma, dOut, desc->ld_act_d, dX,
-                                 desc->ld_act_d, dgp, nblk, c.b, c.dm, s));
-    if (dgamma) HIP_TRY(launch_dgamma_reduce(dgp, c.b > 0 ? nblk : 0, c.dm, dgamma, c.grad_f32, c.bf16, accumulate, s));
-  } else if (c.b > 0) {
-    HIP_TRY(launch_add(c.bf16, dOut, desc->ld_act_d, dUb, c.dm, dX, desc->ld_act_d, c.b, c.dm, s));
-  }
+  if (!dx_first) TRY(norm_backward());
   return MECEFO_OK;
 }
 
