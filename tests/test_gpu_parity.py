@@ -56,6 +56,35 @@ def test_block_bwd_skip_ragged(shape, dtype):
     assert_close(got, oracle_block(c), TOL[dtype], label=f"{shape} {dtype}: ")
 
 
+def _random_cases(n, dtype):
+    rng = np.random.default_rng(20251016)
+    out = []
+    for i in range(n):
+        b = int(rng.integers(1, 700))
+        d = int(rng.integers(1, 90)) * 8 if dtype == "bf16" else int(rng.integers(2, 500))
+        f = int(rng.integers(1, 900))
+        rs = tuple(int(rng.integers(1, min(d, f, 200) + 1)) for _ in range(3))
+        out.append((i, b, d, f, rs, int(rng.integers(0, 3)) * 8, int(rng.integers(0, 3)) * 8, bool(rng.integers(0, 2)),
+                    B.SIDE_INPUT if rng.integers(0, 4) else B.SIDE_OUTPUT))
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_block_bwd_skip_random_shapes(dtype):
+    """Seeded sweep over token counts, widths, per-matrix ranks, row paddings, aliasing and projection
+    side; every case against the oracle."""
+    for i, b, d, f, rs, pad_a, pad_w, alias, side in _random_cases(10, dtype):
+        oside = O.SIDE_INPUT if side == B.SIDE_INPUT else O.SIDE_OUTPUT
+        lim = (d, d, f) if side == B.SIDE_INPUT else (f, f, d)
+        rs = tuple(min(r, l) for r, l in zip(rs, lim))
+        c = make_case(5000 + i, b, d, f, 0, dtype, side=side, rs=rs)
+        lay = Layer(b, d, f, dtype, c["Wg"], c["Wu"], c["Wd"], c["gamma"], c["Pg"], c["Pu"], c["Pd"], EPS,
+                    side=side, pad_act_d=pad_a, pad_w=pad_w)
+        got = lay.block_bwd_skip(c["H"], c["dOut"], alias=alias)
+        assert_close(got, oracle_block(c, oside), TOL[dtype],
+                     label=f"case {i}: b={b} d={d} f={f} r={rs} pads={pad_a},{pad_w} alias={alias} side={side}: ")
+
+
 @pytest.mark.parametrize("alias", [False, True])
 @pytest.mark.parametrize("d", [1024, 1032, 2056, 4104, 8192, 8200])
 def test_norm_kernels_over_row_lengths(d, alias):
