@@ -83,6 +83,29 @@ def test_block_fwd_bf16_materialised_scores_path(batch, seq, d, heads, monkeypat
     print(run_fwd(30, batch, seq, d, 344, heads, "bf16")[-1])
 
 
+def test_fused_attention_random_shapes_forward_then_backward():
+    """Seeded sweep over sequence lengths, batch sizes, head counts and both fused head dimensions: the
+    forward on the GPU, then the standard-mode backward fed with the tensors that forward kept, each
+    against the oracle."""
+    rng = np.random.default_rng(20251017)
+    for i in range(8):
+        dh = int(rng.choice([64, 128]))
+        heads = int(rng.integers(1, 4))
+        batch = int(rng.integers(1, 4))
+        seq = int(rng.integers(1, 600))
+        f = int(rng.integers(1, 40)) * 8
+        pad = int(rng.integers(0, 2)) * 8
+        d = dh * heads
+        label = f"case {i}: B{batch} S{seq} heads {heads} dh {dh} f {f} pad {pad}"
+        p, X, dOut, blk, fwd, got, want, errs = run_fwd(6000 + i, batch, seq, d, f, heads, "bf16", pad=pad)
+        for k in ("H", "Q", "K", "V", "O", "L"):
+            blk.inp[k] = fwd.out[k]
+        res = blk.run()
+        ref = O.block_bwd_full(X, dOut, p, heads, batch, seq, EPS)
+        berrs = assert_close(res, ref, TOL["bf16"], keys=["dX"] + GRADS, label=label + " bwd: ")
+        print(label, max(errs.values()), max(berrs.values()))
+
+
 def test_neighbor_mode_forward_keeps_only_h_and_matches_standard_mode():
     p, X, dOut, blk, fwd, std, want, _ = run_fwd(25, 2, 200, 128, 344, 4, "bf16")
     nb = fwd.run(neighbor=True)
