@@ -75,6 +75,7 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
   a.accumulate = g.accumulate;
   a.out_f32 = g.out_f32;
   a.partial = g.partial;
+  { const char* kr = getenv("MECEFO_KROT"); a.krot = kr ? atoi(kr) : 8; }   // 0 switches the K rotation off (measurement)
   if (tiles == 0) return hipSuccess;
   void (*kern)(const KArgs);
   if constexpr (DTL) kern = gemm_bf16_dtl_kernel<Cfg, Pipe, AKC, BKC, EPI>;

@@ -14,6 +14,7 @@ struct KArgs {
   int out_f32;
   float* partial;
   int64_t partial_off[3];
+  int krot;          // direct-to-LDS kernel: tile row tm starts its K loop at stage tm % krot (0: off)
   // Schedule (filled by fill_schedule): the logical tile order is eight consecutive segments, one
   // per XCD; segment x lists, heaviest problem first, the x-th eighth of every problem's tiles.
   int order[3];         // problem indices, most work per tile first
