@@ -28,12 +28,12 @@ PEAK_HBM_GBS = 8000.0
 # runs of this script), each divided by what the same counter reads for a plain 1 GiB device copy
 # (0.500 and 1.000).  Source and commands: profiles/gemm_bf16_C5_hbm_traffic.md.
 C5_TRAFFIC_BYTES = {
-    "dgrad_down": (1217 + 172) * 2**20,
-    "recompute": (2269 + 516) * 2**20,
-    "dgrad_gate_up": (2064 + 64) * 2**20,
-    "project": (750 + 48) * 2**20,
-    "contract": (1420 + 51) * 2**20,
-    "expand": (578 + 517) * 2**20,
+    "dgrad_down": (1215 + 172) * 2**20,
+    "recompute": (2677 + 516) * 2**20,
+    "dgrad_gate_up": (2080 + 64) * 2**20,
+    "project": (761 + 48) * 2**20,
+    "contract": (1434 + 51) * 2**20,
+    "expand": (630 + 517) * 2**20,
 }
 
 
