@@ -28,6 +28,9 @@
  * (a hipStream_t passed as void*, NULL = default stream) and return without
  * synchronising.  Workspace contents are undefined after a call; two calls that
  * share a workspace must be ordered on the same stream.
+ * Stream capture: the calls are capturable into a HIP graph.  The first launch of a kernel on a
+ * device also raises that kernel's dynamic-LDS limit (hipFuncSetAttribute, host side, once per kernel
+ * and device), so run each call once eagerly with the shapes in use before capturing it.
  *
  * Layout rules: every matrix is row-major with an explicit row stride in elements.
  * dtype MECEFO_BF16: storage bf16, fp32 accumulation in MFMA; all data pointers must
