@@ -363,6 +363,21 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
           ep[o] = acc[i][j][e];
           if constexpr (DUAL) ep[MAT + o] = acc[i][j + TN / 2][e];
         }
+      // fp32 outputs: four columns per lane, so that one store instruction covers whole 512-byte row
+      // pieces (with eight columns per lane each of the two 16-byte stores would fill every other
+      // 16 bytes of its lines)
+      if ((EPI == EPI_GRAD && args.out_f32) || EPI == EPI_SPLIT_F32) {
+        constexpr int LPR4 = W / 4, RPI4 = 64 / LPR4;
+        const int r4 = lane / LPR4, c4 = (lane % LPR4) * 4;
+#pragma unroll
+        for (int it = 0; it < 32 / RPI4; ++it) {
+          const int rl = it * RPI4 + r4;
+          const f32x4_t g = *(const f32x4_t*)(ep + rl * RS + c4);
+          const float v4[4] = {g[0], g[1], g[2], g[3]}, z4[4] = {0.f, 0.f, 0.f, 0.f};
+          epilogue_vec4<EPI>(p, args, tc.prob, tc.split, row_w + i * 32 + rl, col_w - rd_c8 + c4, v4, z4);
+        }
+        continue;
+      }
 #pragma unroll
       for (int it = 0; it < 32 / RPI; ++it) {
         const int rl = it * RPI + rd_row;
