@@ -155,7 +155,15 @@ int choose_splits(const Ctx& c, const int64_t c_rows[3], const int r[3]) {
   int tiles, ktiles, target;
   if (!c.bf16) { tiles = tiles_f; ktiles = cdiv((int)c.b, 16); target = 512; }
   else if (tiles_l >= 160) { tiles = tiles_l; ktiles = cdiv((int)c.b, 64); target = 256; }
-  else { tiles = tiles_s; ktiles = cdiv((int)c.b, 64); target = 512; }
+  else {
+    // Mid-size layers: 256 x 256 tiles on the direct-to-LDS kernel, cut along the tokens into just
+    // enough parts for half the chip, beat 128 x 128 tiles as long as every part keeps eight K
+    // stages (the launcher applies the same rule when it picks the tile configuration).
+    ktiles = cdiv((int)c.b, 64);
+    const int s_l = tiles_l > 0 ? cdiv(128, tiles_l) : 0;
+    if (s_l >= 1 && s_l <= 16 && ktiles / s_l >= 8) return s_l;
+    tiles = tiles_s; target = 512;
+  }
   if (tiles == 0) return 1;
   int s = cdiv(target, tiles);
   const int smax = ktiles / 4 > 1 ? ktiles / 4 : 1;

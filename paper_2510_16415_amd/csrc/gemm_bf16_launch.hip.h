@@ -20,7 +20,22 @@ inline int bf16_tiles(const GemmLaunch& g, int bm, int bn) {
     t += cdiv(g.p[i].M, bm) * cdiv(g.p[i].N, dual ? bn / 2 : bn) * (g.p[i].batch > 1 ? g.p[i].batch : 1);
   return t;
 }
-inline bool bf16_use_large(const GemmLaunch& g) { return bf16_tiles(g, 256, 256) >= 160; }
+// 256 x 256 tiles (direct-to-LDS kernel) when they give at least half of the 256 CUs a tile; a
+// split-K launch counts its parts, provided each keeps eight or more K stages.  Below that the
+// 128 x 128 configuration fills the chip better.
+inline bool bf16_use_large(const GemmLaunch& g) {
+  const int tl = bf16_tiles(g, 256, 256);
+  if (tl >= 128) return true;
+  if (g.epi == EPI_SPLIT_F32 && g.splits > 1) {
+    int stages = 1 << 30;
+    for (int i = 0; i < g.nprob; ++i) {
+      const int st = cdiv(g.p[i].K, 64) * (g.p[i].nseg > 1 ? g.p[i].nseg : 1);
+      if (st < stages) stages = st;
+    }
+    return tl * g.splits >= 128 && stages / g.splits >= 8;
+  }
+  return false;
+}
 
 // The direct-to-LDS kernel cannot mask a ragged K inside a 16-byte chunk.
 inline bool bf16_dtl_ok(const GemmLaunch& g) {
