@@ -187,14 +187,19 @@ int store_splits_du(const Ctx& c) {   // dU [b x d], two K segments of length f
   return store_splits(c.bf16, cdiv((int)c.b, 256) * cdiv(c.dm, 256), 2 * cdiv(c.ff, 64));
 }
 int store_splits_project(const Ctx& c, const int r[3], mecefo_side_t side) {   // T_i [b x r_i]
-  int tiles = 0, stages = 1 << 30;
+  int tiles = 0, stages = 0;
   for (int i = 0; i < 3; ++i) {
     if (r[i] <= 0) continue;
     tiles += cdiv((int)c.b, 256) * cdiv(r[i], 256);
     const int k = side == MECEFO_SIDE_INPUT ? (i < 2 ? c.dm : c.ff) : (i < 2 ? c.ff : c.dm);
-    if (cdiv(k, 64) < stages) stages = cdiv(k, 64);
+    if (cdiv(k, 64) > stages) stages = cdiv(k, 64);      // the longest contraction sets the pace of the launch
   }
-  return tiles > 0 ? store_splits(c.bf16, tiles, stages) : 1;
+  if (tiles <= 0 || !c.bf16 || tiles >= 128 || stages < 16) return 1;
+  // as many parts as fit the chip in one go, none shorter than four K stages of the longest problem
+  int sp = 256 / tiles;
+  if (sp > stages / 4) sp = stages / 4;
+  if (sp > 8) sp = 8;
+  return sp < 1 ? 1 : sp;
 }
 
 Workspace layout(const Ctx& c, const int r[3], mecefo_side_t side, int force_splits) {
