@@ -37,9 +37,9 @@ int fail(int st, const char* fmt, ...) {
 
 namespace {
 
-template <typename... T> mecefo_status_t fail(mecefo_status_t st, const char* fmt, T... a) {
-  return (mecefo_status_t)mecefo::fail((int)st, fmt, a...);
-}
+// Status-typed front of mecefo::fail; a macro so that the compiler still checks the format string
+// against the arguments at every call site.
+#define fail(st, ...) ((mecefo_status_t)mecefo::fail((int)(st), __VA_ARGS__))
 
 constexpr int64_t kMaxBytes = (int64_t)1 << 31;
 
