@@ -102,6 +102,14 @@ struct DmaKC {   // K-contiguous source; one wave instruction covers RPI consecu
 };
 
 __device__ inline int ks_swz(int k) { return (k & 7) << 1; }   // XOR on the 16-byte chunk index
+// Physical 16-byte chunk of logical chunk c (0..31, eight columns each) in k row k, and back.  A
+// transposing read takes, per pass of 32 lanes, 64 bytes (four chunks) of each of four consecutive k
+// rows; LDS serves 256 bytes per clock from 64 banks, so the 16 chunks of a pass must differ in their
+// low four bits.  The k row fills bits 1-2 (XOR with k), the second chunk pair of a row (bit 1 of c)
+// moves to the other half of the banks (bit 3).  The map is its own inverse.
+__device__ inline int ks_fold(int c) { return c ^ ((c & 2) << 2); }
+__device__ inline int ks_phys(int c, int k) { return (ks_fold(c) ^ ks_swz(k)) & 31; }
+__device__ inline int ks_logical(int pos, int k) { return ks_fold((pos ^ ks_swz(k)) & 31); }
 
 template <int BK, int NT>
 struct DmaKS {   // K-strided source; wave instruction g covers k rows 2g, 2g+1 (512 bytes each)
@@ -114,7 +122,7 @@ struct DmaKS {   // K-strided source; wave instruction g covers k rows 2g, 2g+1 
   __device__ inline void init(int lane, int wave, int row_base, int rows_total, int64_t ld) {
     w = wave;
     krow0 = 2 * w + (lane >> 5);
-    const int cm = (lane & 31) ^ ks_swz(krow0);     // rows 16 q apart share k & 7
+    const int cm = ks_logical(lane & 31, krow0);     // rows 16 q apart share k & 7
     const int m = row_base + cm * 8;
     ld2 = (uint32_t)(ld * 2);
     voff = m < rows_total ? (uint32_t)(((int64_t)krow0 * ld + m) * 2) : kOOB;
@@ -167,7 +175,7 @@ struct FragKS {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int k = 8 * hi + 4 * h + kq;
-        base[i][h] = k * 512 + ((((m >> 3) ^ ks_swz(k)) & 31) << 4) + ((m & 7) << 1);
+        base[i][h] = k * 512 + (ks_phys(m >> 3, k) << 4) + ((m & 7) << 1);
       }
     }
   }
