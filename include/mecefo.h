@@ -30,7 +30,8 @@
  * share a workspace must be ordered on the same stream.
  * Stream capture: the calls are capturable into a HIP graph.  The first launch of a kernel on a
  * device also raises that kernel's dynamic-LDS limit (hipFuncSetAttribute, host side, once per kernel
- * and device), so run each call once eagerly with the shapes in use before capturing it.
+ * and device); mecefo_init() does that for every kernel of the library up front, so a caller that
+ * captures calls it once per device before the capture (no eager warm-up run is needed).
  *
  * Layout rules: every matrix is row-major with an explicit row stride in elements.
  * dtype MECEFO_BF16: storage bf16, fp32 accumulation in MFMA; all data pointers must
@@ -195,8 +196,8 @@ typedef struct {
 /* Workspace: a few [b x d] activations and one [b x ld_act_f] activation.  bf16 with head dimension
  * 64 or 128 runs the attention as one fused kernel (running maximum and sum per query, no score
  * buffer); other shapes add fp32 scores and probabilities of a chunk of heads (at most 256 MiB of
- * scores).  The environment variable MECEFO_ATTN=gemm selects the second form everywhere (testing);
- * it is read by the query and by the call, so set it before both. */
+ * scores).  mecefo_set_option("attention", "gemm") selects the second form everywhere (testing); the
+ * query and the call consult the same switch, so set it before both. */
 mecefo_status_t mecefo_block_fwd_workspace_bytes(const mecefo_ffn_desc_t* desc,
     const mecefo_attn_desc_t* attn, size_t* out_bytes);
 mecefo_status_t mecefo_block_fwd(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
@@ -328,6 +329,18 @@ typedef enum {
 } mecefo_stage_t;
 mecefo_status_t mecefo_profile_enable(int max_stage_launches);
 mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_stage);
+
+/* Prepares the current device: raises the dynamic-LDS limit of every kernel that needs more than the
+ * default (what the first launch of each kernel would otherwise do on the host).  Optional; for callers
+ * that capture the calls into a HIP graph without running them eagerly first.  Idempotent, cheap after
+ * the first call on a device, safe from several host threads. */
+mecefo_status_t mecefo_init(void);
+
+/* Process-wide switches for tests and measurements (not needed for normal use; the library chooses
+ * by shape).  name "tile": bf16 GEMM configuration, value "auto" | "S" (128x128) | "L4" | "L8R" (256x256,
+ * register-staged) | "L8" (256x256, direct-to-LDS).  name "attention": "auto" | "gemm" (batched GEMM
+ * launches instead of the fused attention kernels).  Affects calls made after it returns. */
+mecefo_status_t mecefo_set_option(const char* name, const char* value);
 
 /* Description of the last non-OK status returned on this thread ("" if none). */
 const char* mecefo_last_error(void);

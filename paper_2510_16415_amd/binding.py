@@ -123,6 +123,10 @@ def lib() -> C.CDLL:
     L.mecefo_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
     L.mecefo_profile_enable.restype = C.c_int
     L.mecefo_profile_collect.restype = C.c_int
+    L.mecefo_init.argtypes = []
+    L.mecefo_init.restype = C.c_int
+    L.mecefo_set_option.argtypes = [C.c_char_p, C.c_char_p]
+    L.mecefo_set_option.restype = C.c_int
     for f in ("mecefo_workspace_bytes", "mecefo_ffn_fwd_recompute", "mecefo_ffn_bwd_exact",
               "mecefo_ffn_bwd_lowrank", "mecefo_block_bwd_skip", "mecefo_block_full_workspace_bytes",
               "mecefo_block_bwd_full", "mecefo_projection_workspace_bytes", "mecefo_projection_refresh",
@@ -335,6 +339,14 @@ def mecefo_profile_collect():
     cnt = (C.c_int * n)()
     _check(lib().mecefo_profile_collect(ms, cnt))
     return {STAGES[i]: (ms[i], cnt[i]) for i in range(n) if cnt[i]}
+
+
+def mecefo_init():
+    _check(lib().mecefo_init())
+
+
+def mecefo_set_option(name: str, value: str):
+    _check(lib().mecefo_set_option(name.encode(), value.encode()))
 
 
 def mecefo_last_error() -> str:

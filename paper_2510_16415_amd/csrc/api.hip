@@ -24,6 +24,11 @@ hipError_t launch_gemm(GemmLaunch& g, hipStream_t s) {
 }  // namespace mecefo
 
 namespace mecefo {
+Options& options() {
+  static Options o;
+  return o;
+}
+
 thread_local char g_err[512] = "";
 
 int fail(int st, const char* fmt, ...) {
@@ -92,6 +97,19 @@ mecefo_status_t check_desc(const mecefo_ffn_desc_t* d, Ctx* c) {
 mecefo_status_t check_ptr(const Ctx& c, const void* p, const char* name, bool required = true) {
   if (!p) return required ? fail(MECEFO_ERR_INVALID_ARG, "%s is NULL", name) : MECEFO_OK;
   if (((uintptr_t)p) % (c.bf16 ? 16 : 4)) return fail(MECEFO_ERR_INVALID_ARG, "%s is not %d-byte aligned", name, c.bf16 ? 16 : 4);
+  return MECEFO_OK;
+}
+
+// Bytes spanned by a [b x d_model] activation tensor with row stride ld.
+size_t act_span(const Ctx& c, int64_t ld) { return c.b > 0 ? (size_t)(((c.b - 1) * ld + c.dm) * c.esz) : 0; }
+
+// An output may coincide with an input it is allowed to overwrite (same pointer), or lie apart from it;
+// a partial overlap would let the kernels read rows that are already overwritten.
+mecefo_status_t check_alias(const void* out, const char* out_name, const void* in, const char* in_name, size_t bytes) {
+  if (!out || !in || out == in || bytes == 0) return MECEFO_OK;
+  const uintptr_t a = (uintptr_t)out, b = (uintptr_t)in;
+  if (a < b + bytes && b < a + bytes)
+    return fail(MECEFO_ERR_INVALID_ARG, "%s overlaps %s without being equal to it", out_name, in_name);
   return MECEFO_OK;
 }
 
@@ -508,11 +526,10 @@ struct FwdWs {
 };
 
 // The block forward takes the fused attention kernel (no score or probability buffer) whenever it is
-// built for the shape; MECEFO_ATTN=gemm keeps the materialised-score form for testing.  The
+// built for the shape; mecefo_set_option("attention", "gemm") keeps the materialised-score form for testing.  The
 // workspace query and the call consult the same predicate.
 bool fwd_attention_fused(const Ctx& c, const mecefo_attn_desc_t& a) {
-  const char* env = getenv("MECEFO_ATTN");
-  if (env && env[0] == 'g') return false;
+  if (options().attn_gemm.load(std::memory_order_relaxed)) return false;
   // bf16 descriptors have row strides that are multiples of 8 (checked with the descriptor)
   return attn_fwd_fused_supported(c.bf16, c.dm / (a.heads > 0 ? a.heads : 1), a.seq > 0 ? a.seq : 1, 8);
 }
@@ -558,7 +575,32 @@ mecefo_status_t check_lowrank_args(const Ctx& c, const mecefo_proj_t P[3], mecef
 extern "C" {
 
 const char* mecefo_last_error(void) { return g_err; }
-const char* mecefo_version(void) { return "mecefo-gfx950 0.1"; }
+const char* mecefo_version(void) { return "mecefo-gfx950 0.2"; }
+
+mecefo_status_t mecefo_init(void) {
+  HIP_TRY(prepare_gemm_bf16_nt());
+  HIP_TRY(prepare_gemm_bf16_nn());
+  HIP_TRY(prepare_gemm_bf16_tn());
+  HIP_TRY(prepare_attention_fwd());
+  HIP_TRY(prepare_attention_bwd());
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_set_option(const char* name, const char* value) {
+  if (!name || !value) return fail(MECEFO_ERR_INVALID_ARG, "option name and value are required");
+  if (!strcmp(name, "tile")) {
+    static const char* const names[5] = {"auto", "S", "L4", "L8R", "L8"};
+    for (int i = 0; i < 5; ++i)
+      if (!strcmp(value, names[i])) { options().tile.store(i, std::memory_order_relaxed); return MECEFO_OK; }
+    return fail(MECEFO_ERR_INVALID_ARG, "option tile: value must be auto, S, L4, L8R or L8 (got %s)", value);
+  }
+  if (!strcmp(name, "attention")) {
+    if (!strcmp(value, "auto")) { options().attn_gemm.store(0, std::memory_order_relaxed); return MECEFO_OK; }
+    if (!strcmp(value, "gemm")) { options().attn_gemm.store(1, std::memory_order_relaxed); return MECEFO_OK; }
+    return fail(MECEFO_ERR_INVALID_ARG, "option attention: value must be auto or gemm (got %s)", value);
+  }
+  return fail(MECEFO_ERR_INVALID_ARG, "unknown option %s", name);
+}
 
 mecefo_status_t mecefo_profile_enable(int max_launches) {
   if (max_launches < 1) return fail(MECEFO_ERR_INVALID_ARG, "max_launches must be >= 1");
@@ -706,6 +748,8 @@ mecefo_status_t mecefo_block_bwd_skip_ex(const mecefo_ffn_desc_t* desc, const vo
   if (!dWg || !dWu || !dWd) return fail(MECEFO_ERR_INVALID_ARG, "dWg, dWu, dWd are required");
   if (c.bf16 && (((uintptr_t)dWg | (uintptr_t)dWu | (uintptr_t)dWd) % 16)) return fail(MECEFO_ERR_INVALID_ARG, "gradient buffers must be 16-byte aligned");
   if (dgamma && !gamma) return fail(MECEFO_ERR_INVALID_ARG, "dgamma requested but gamma is NULL");
+  TRY(check_alias(dX, "dX", dOut, "dOut", act_span(c, desc->ld_act_d)));
+  TRY(check_alias(dX, "dX", H, "H", act_span(c, desc->ld_act_d)));
   const mecefo_proj_t P[3] = {Pg, Pu, Pd};
   TRY(check_lowrank_args(c, P, side, exact_mask));
   const int r[3] = {(exact_mask & 1) ? 0 : Pg.r, (exact_mask & 2) ? 0 : Pu.r, (exact_mask & 4) ? 0 : Pd.r};
@@ -873,8 +917,8 @@ mecefo_status_t mecefo_block_bwd_full(const mecefo_ffn_desc_t* desc, const mecef
       STAGE(MECEFO_STAGE_ATTN_ROWDOT, s);
       HIP_TRY(launch_attn_rowdot(c.bf16, dO, dm, in->O, d.ld_act_d, D, c.b, S, a.heads, dh, s));
     }
-    const char* attn_env = getenv("MECEFO_ATTN");     // "gemm" forces the five-product form
-    const bool fused = attn_bwd_fused_supported(c.bf16, dh, S, w.ldp) && !(attn_env && attn_env[0] == 'g');
+    // mecefo_set_option("attention", "gemm") forces the five-product form
+    const bool fused = attn_bwd_fused_supported(c.bf16, dh, S, w.ldp) && !options().attn_gemm.load(std::memory_order_relaxed);
     if (fused) {  // dK, dV and dS in one kernel; P stays in registers
       STAGE(MECEFO_STAGE_ATTN_FUSED_KV, s);
       HIP_TRY(launch_attn_bwd_kv(in->Q, in->K, in->V, d.ld_act_d, dO, dK, dV, dm, in->L, D, P, w.ldp, a.batch, S,

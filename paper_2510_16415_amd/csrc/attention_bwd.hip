@@ -316,6 +316,16 @@ bool attn_bwd_fused_supported(bool bf16, int dh, int seq, int64_t ldp) {
 }
 
 // Q, K, V: caller tensors (row stride ld_in); dO, dK, dV: workspace tensors (row stride ld_ws).
+static hipError_t attn_bwd_limit(int dh) {
+  static LdsLimitOnce limit[2];
+  void (*kern)(const AttnBwdArgs) = dh == 128 ? attn_bwd_kv_kernel<128> : attn_bwd_kv_kernel<64>;
+  return limit[dh == 128].ensure((const void*)kern, 4 * kBr * dh * 2 + 4 * kBr * 4);
+}
+hipError_t prepare_attention_bwd() {
+  const hipError_t e = attn_bwd_limit(64);
+  return e != hipSuccess ? e : attn_bwd_limit(128);
+}
+
 hipError_t launch_attn_bwd_kv(const void* Q, const void* K, const void* V, int64_t ld_in, const void* dO,
                               void* dK, void* dV, int64_t ld_ws, const float* L, const float* D, void* dS,
                               int64_t ldp, int batch, int seq, int heads, int dh, float scale, hipStream_t s) {
@@ -330,8 +340,7 @@ hipError_t launch_attn_bwd_kv(const void* Q, const void* K, const void* V, int64
   const dim3 grid((unsigned)(a.nz * a.nkb));
   const int lds = 4 * kBr * dh * 2 + 4 * kBr * 4;
   void (*kern)(const AttnBwdArgs) = dh == 128 ? attn_bwd_kv_kernel<128> : attn_bwd_kv_kernel<64>;
-  static LdsLimitOnce limit[2];
-  const hipError_t e = limit[dh == 128].ensure((const void*)kern, lds);
+  const hipError_t e = attn_bwd_limit(dh);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a);
   return hipGetLastError();

@@ -222,6 +222,16 @@ bool attn_fwd_fused_supported(bool bf16, int dh, int seq, int64_t ld) {
 }
 
 // Q, K, V, O: token-major [batch*seq x ld], head h at columns h*dh; L [batch*heads*seq] fp32.
+static hipError_t attn_fwd_limit(int dh) {
+  static LdsLimitOnce limit[2];
+  void (*kern)(const AttnFwdArgs) = dh == 128 ? attn_fwd_kernel<128> : attn_fwd_kernel<64>;
+  return limit[dh == 128].ensure((const void*)kern, 4 * kFk * dh * 2);
+}
+hipError_t prepare_attention_fwd() {
+  const hipError_t e = attn_fwd_limit(64);
+  return e != hipSuccess ? e : attn_fwd_limit(128);
+}
+
 hipError_t launch_attn_fwd(const void* Q, const void* K, const void* V, void* O, int64_t ld, float* L, int batch,
                            int seq, int heads, int dh, float scale, hipStream_t s) {
   AttnFwdArgs a;
@@ -232,8 +242,7 @@ hipError_t launch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
   if (a.nz == 0 || seq == 0) return hipSuccess;
   const int lds = 4 * kFk * dh * 2;
   void (*kern)(const AttnFwdArgs) = dh == 128 ? attn_fwd_kernel<128> : attn_fwd_kernel<64>;
-  static LdsLimitOnce limit[2];
-  const hipError_t e = limit[dh == 128].ensure((const void*)kern, lds);
+  const hipError_t e = attn_fwd_limit(dh);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.nz * a.nqb)), dim3(256), lds, s, a);
   return hipGetLastError();

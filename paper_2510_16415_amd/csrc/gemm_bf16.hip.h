@@ -187,9 +187,7 @@ template <int R, int NT, bool DUAL> struct LoaderSel<R, NT, false, DUAL> {
   using type = LoaderKS<R, NT>;
 };
 
-// DBG (experiments only, 0 in every product instantiation): bit 0 skips the global loads after
-// the first stage, bit 1 also skips the LDS stores, to bound what the memory pipeline costs.
-template <class Cfg, bool AKC, bool BKC, int EPI, int DBG = 0>
+template <class Cfg, bool AKC, bool BKC, int EPI>
 __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
   constexpr bool DUAL = epi_is_dual(EPI);
   // fp32 outputs (gradients, split-K partials): issue the MFMA with swapped operands so that a
@@ -297,14 +295,14 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_kernel(const KArgs args) {
       const uint8_t* sb = sa + Cfg::A_BYTES;
       uint8_t* na = smem + (cur ^ 1) * Cfg::STAGE_BYTES;
       const bool more = kt + 1 < kt_end;
-      if (more && !(DBG & 1)) issue_loads(kt + 1);
+      if (more) issue_loads(kt + 1);
       fetch(1, sa, sb, 1);
       mma(0);
       fetch(0, sa, sb, 2);
       mma(1);
       fetch(1, sa, sb, 3);
       mma(0);
-      if (more && !(DBG & 2)) {
+      if (more) {
         la.store(na);
         lb.store(na + Cfg::A_BYTES);
       }

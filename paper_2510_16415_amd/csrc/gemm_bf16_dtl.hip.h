@@ -206,13 +206,9 @@ template <int BK_, int NS_> struct DtlPipe {
   static_assert(32 * 136 * 4 <= EP_WAVE_BYTES, "epilogue slice too small");
 };
 
-// DBG (experiments only, 0 in every product instantiation): bit 0 skips the refills, bit 1 makes
-// every refill fetch K offset 0 (cache-resident), bit 2 skips the B refills, bit 3 skips the
-// fragment fetches and MFMAs (fill traffic only).
-template <class Cfg, class Pipe, bool AKC, bool BKC, int EPI, int DBG = 0>
+template <class Cfg, class Pipe, bool AKC, bool BKC, int EPI>
 __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args) {
   constexpr bool DUAL = epi_is_dual(EPI);
-  constexpr bool SWAP = false;   // every epilogue of this kernel is staged through LDS
   constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::NT;
   constexpr int BK = Pipe::BK, NS = Pipe::NS, KS = BK / 16, FPS = BK / 8;
   constexpr int A_BYTES = Pipe::A_BYTES, STAGE = Pipe::STAGE_BYTES;
@@ -275,14 +271,14 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
 
   auto issue = [&](int kt, uint32_t stage) {
     const int seg = (kt >= kt_per_seg ? 1 : 0) + (kt >= 2 * kt_per_seg ? 1 : 0);
-    const int k0 = (DBG & 2) ? 0 : (kt - seg * kt_per_seg) * BK;
+    const int k0 = (kt - seg * kt_per_seg) * BK;
     const bool tail = k0 + BK > K;
     if (DUAL) {
       da.issue(ra0, ra0, stage, k0, K, tail);
       db.issue(rb0, rb1, stage + A_BYTES, k0, K, tail);
     } else {
       da.issue(select_rsrc(seg, ra0, ra1, ra2), ra0, stage, k0, K, tail);
-      if (!(DBG & 4)) db.issue(select_rsrc(seg, rb0, rb1, rb2), rb0, stage + A_BYTES, k0, K, tail);
+      db.issue(select_rsrc(seg, rb0, rb1, rb2), rb0, stage + A_BYTES, k0, K, tail);
     }
   };
 
@@ -292,8 +288,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0)
-                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
   };
 
   const int nst = kt_end - kt_begin;
@@ -324,7 +319,6 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
       const int nbuf = buf + 1 == NS ? 0 : buf + 1;
 #pragma unroll
       for (int ks = 0; ks + 1 < KS; ++ks) {
-        if (DBG & 8) break;
         fa.fetch(af[(ks + 1) & 1], sc, ks + 1);
         fb.fetch(bfr[(ks + 1) & 1], sc + A_BYTES, ks + 1);
         mma(ks & 1);
@@ -333,12 +327,12 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
       // fills stay in flight), meet the other waves, then refill this buffer NS stages ahead.
       wait_fills_leave<FPS>(min(NS - 2, kt_end - kt - 2));
       __syncthreads();
-      if (kt + NS < kt_end && !(DBG & 1)) issue(kmap(kt - kt_begin + NS), smem_addr + buf * STAGE);
-      if (kt + 1 < kt_end && !(DBG & 8)) {
+      if (kt + NS < kt_end) issue(kmap(kt - kt_begin + NS), smem_addr + buf * STAGE);
+      if (kt + 1 < kt_end) {
         fa.fetch(af[0], smem + nbuf * STAGE, 0);
         fb.fetch(bfr[0], smem + nbuf * STAGE + A_BYTES, 0);
       }
-      if (!(DBG & 8)) mma((KS - 1) & 1);
+      mma((KS - 1) & 1);
       buf = nbuf;
     }
   }
@@ -349,7 +343,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
   // into its own LDS slice (row stride RS floats, chosen so that the two half-waves hit
   // different banks), then reads rows back eight columns per lane.  The operand stages are
   // free at this point: the loop's last barrier followed every fragment fetch and every fill.
-  if constexpr (!SWAP) {
+  {
     constexpr int TNO = DUAL ? TN / 2 : TN;
     constexpr int W = TNO * 32;                 // columns per matrix in this wave's sub-tile
     constexpr int RS = W + 8;                   // 4*RS % 64 == 32
@@ -402,29 +396,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
         epilogue_vec8<EPI>(p, args, tc.prob, tc.split, row_w + i * 32 + rl, col_w, v, v2);
       }
     }
-    return;
   }
-  // Swapped operands: the B fragment was the MFMA's row operand, so a lane holds, for
-  // block (i, j), output row lane%32 and the four consecutive columns 8*g + 4*(lane/32) + 0..3
-  // in accumulator elements 4g..4g+3 (g = 0..3): stores are 8 or 16 bytes wide.
-  const int lrow = lane & 31;
-  const int row_w = m0 + wm * Cfg::WM + lrow;
-  constexpr int TNO = DUAL ? TN / 2 : TN;
-  const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + 4 * (lane >> 5);
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TNO; ++j)
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        float v[4], v2[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          v[e] = acc[i][j][4 * g4 + e];
-          v2[e] = DUAL ? acc[i][DUAL ? j + TN / 2 : j][4 * g4 + e] : 0.f;
-        }
-        epilogue_vec4<EPI>(p, args, tc.prob, tc.split, row_w + i * 32, col_w + j * 32 + 8 * g4, v, v2);
-      }
 }
 
 }  // namespace mecefo

@@ -1,7 +1,5 @@
 // Host-side launch helpers for the bf16 MFMA GEMM instantiations.
 #pragma once
-#include <stdlib.h>
-
 #include "gemm_bf16_dtl.hip.h"
 
 namespace mecefo {
@@ -45,13 +43,11 @@ inline bool bf16_dtl_ok(const GemmLaunch& g) {
 }
 
 // 0: 128x128 / 4 waves, 1: 256x256 / 4 waves, 2: 256x256 / 8 waves (register staging),
-// 3: 256x256 / 8 waves, direct-to-LDS, 2 x 64-K stages.
-// Tuning knob for experiments: MECEFO_TILE = S | L4 | L8R | L8 forces one configuration.
+// 3: 256x256 / 8 waves, direct-to-LDS, 2 x 64-K stages.  mecefo_set_option("tile", ...) forces one.
 inline int bf16_tile_choice(const GemmLaunch& g) {
-  const char* env = getenv("MECEFO_TILE");   // read per launch so that tests can switch it
   int c = (bf16_use_large(g) || g.force_large) ? 3 : 0;
-  if (env && env[0] == 'S') c = 0;
-  if (env && env[0] == 'L') c = env[1] == '4' ? 1 : (env[2] == 'R' ? 2 : 3);
+  const int forced = options().tile.load(std::memory_order_relaxed);
+  if (forced >= 1 && forced <= 4) c = forced - 1;
   if (c >= 3 && !bf16_dtl_ok(g)) c = 2;
   return c;
 }
@@ -64,10 +60,25 @@ using PipeA = DtlPipe<64, 2>;
 
 struct NoPipe { static constexpr int LDS_BYTES = 0; };
 
+// One kernel instantiation: its entry point, its dynamic LDS size and the once-per-device limit raise.
+template <class Cfg, bool AKC, bool BKC, int EPI, class Pipe>
+struct Bf16Kernel {
+  static constexpr bool DTL = Pipe::LDS_BYTES > 0;
+  static constexpr int LDS = DTL ? Pipe::LDS_BYTES : Cfg::LDS_BYTES;
+  static auto entry() -> void (*)(const KArgs) {
+    if constexpr (DTL) return gemm_bf16_dtl_kernel<Cfg, Pipe, AKC, BKC, EPI>;
+    else return gemm_bf16_kernel<Cfg, AKC, BKC, EPI>;
+  }
+  static hipError_t prepare() {
+    static LdsLimitOnce limit;
+    return limit.ensure((const void*)entry(), LDS);
+  }
+};
+
 template <class Cfg, bool AKC, bool BKC, int EPI, class Pipe = NoPipe>
 hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
-  constexpr bool DTL = Pipe::LDS_BYTES > 0;
-  constexpr int LDS = DTL ? Pipe::LDS_BYTES : Cfg::LDS_BYTES;
+  using Kern = Bf16Kernel<Cfg, AKC, BKC, EPI, Pipe>;
+  constexpr int LDS = Kern::LDS;
   constexpr bool DUAL = epi_is_dual(EPI);
   KArgs a;
   a.nprob = g.nprob;
@@ -90,16 +101,22 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
   a.accumulate = g.accumulate;
   a.out_f32 = g.out_f32;
   a.partial = g.partial;
-  { const char* kr = getenv("MECEFO_KROT"); a.krot = kr ? atoi(kr) : 8; }   // 0 switches the K rotation off (measurement)
+  a.krot = 8;
   if (tiles == 0) return hipSuccess;
-  void (*kern)(const KArgs);
-  if constexpr (DTL) kern = gemm_bf16_dtl_kernel<Cfg, Pipe, AKC, BKC, EPI>;
-  else kern = gemm_bf16_kernel<Cfg, AKC, BKC, EPI>;
-  static LdsLimitOnce limit;      // one per template instantiation, i.e. per kernel
-  const hipError_t e = limit.ensure((const void*)kern, LDS);
+  const hipError_t e = Kern::prepare();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, dim3(tiles * a.splits), dim3(Cfg::NT), LDS, stream, a);
+  hipLaunchKernelGGL(Kern::entry(), dim3(tiles * a.splits), dim3(Cfg::NT), LDS, stream, a);
   return hipGetLastError();
+}
+
+// Limit raise for the four configurations of one (layout, epilogue) pair.
+template <bool AKC, bool BKC, int EPI>
+hipError_t prepare_bf16() {
+  hipError_t e = Bf16Kernel<CfgS, AKC, BKC, EPI, NoPipe>::prepare();
+  if (e == hipSuccess) e = Bf16Kernel<CfgL4, AKC, BKC, EPI, NoPipe>::prepare();
+  if (e == hipSuccess) e = Bf16Kernel<CfgL8, AKC, BKC, EPI, NoPipe>::prepare();
+  if (e == hipSuccess) e = Bf16Kernel<CfgL8, AKC, BKC, EPI, PipeA>::prepare();
+  return e;
 }
 
 template <bool AKC, bool BKC, int EPI>

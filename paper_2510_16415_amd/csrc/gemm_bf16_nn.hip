@@ -10,4 +10,11 @@ hipError_t launch_gemm_bf16_nn(GemmLaunch& g, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 }
+hipError_t prepare_gemm_bf16_nn() {
+  hipError_t e = hipSuccess;
+  if (e == hipSuccess) e = prepare_bf16<true, false, EPI_STORE>();
+  if (e == hipSuccess) e = prepare_bf16<true, false, EPI_GRAD>();
+  if (e == hipSuccess) e = prepare_bf16<true, false, EPI_SPLIT_F32>();
+  return e;
+}
 }  // namespace mecefo

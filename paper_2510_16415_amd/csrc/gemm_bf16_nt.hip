@@ -15,4 +15,15 @@ hipError_t launch_gemm_bf16_nt(GemmLaunch& g, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 }
+hipError_t prepare_gemm_bf16_nt() {
+  hipError_t e = hipSuccess;
+  if (e == hipSuccess) e = prepare_bf16<true, true, EPI_STORE>();
+  if (e == hipSuccess) e = prepare_bf16<true, true, EPI_GRAD>();
+  if (e == hipSuccess) e = prepare_bf16<true, true, EPI_SPLIT_F32>();
+  if (e == hipSuccess) e = prepare_bf16<true, true, EPI_SWIGLU_FWD>();
+  if (e == hipSuccess) e = prepare_bf16<true, true, EPI_SWIGLU_BWD>();
+  if (e == hipSuccess) e = prepare_bf16<true, true, EPI_ATTN_P>();
+  if (e == hipSuccess) e = prepare_bf16<true, true, EPI_ATTN_DS>();
+  return e;
+}
 }  // namespace mecefo

@@ -10,4 +10,11 @@ hipError_t launch_gemm_bf16_tn(GemmLaunch& g, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 }
+hipError_t prepare_gemm_bf16_tn() {
+  hipError_t e = hipSuccess;
+  if (e == hipSuccess) e = prepare_bf16<false, false, EPI_STORE>();
+  if (e == hipSuccess) e = prepare_bf16<false, false, EPI_SPLIT_F32>();
+  if (e == hipSuccess) e = prepare_bf16<false, false, EPI_GRAD>();
+  return e;
+}
 }  // namespace mecefo

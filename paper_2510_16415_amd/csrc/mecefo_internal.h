@@ -84,6 +84,22 @@ struct LdsLimitOnce {
   }
 };
 
+// Process-wide switches behind mecefo_set_option (tests and measurements; 0 = the library decides).
+struct Options {
+  std::atomic<int> tile{0};        // bf16 GEMM configuration: 1 = 128x128, 2 = 256x256 / 4 waves, 3 = 256x256 / 8 waves
+                                   // register-staged, 4 = 256x256 / 8 waves direct-to-LDS
+  std::atomic<int> attn_gemm{0};   // 1: attention through batched GEMM launches instead of the fused kernels
+};
+Options& options();
+
+// Raise the dynamic-LDS limit of every kernel that needs it on the current device (what the first
+// launch of each kernel would otherwise do): mecefo_init.
+hipError_t prepare_gemm_bf16_nt();
+hipError_t prepare_gemm_bf16_nn();
+hipError_t prepare_gemm_bf16_tn();
+hipError_t prepare_attention_fwd();
+hipError_t prepare_attention_bwd();
+
 // Returns hipSuccess or the launch error.  Only enqueues.
 hipError_t launch_gemm(GemmLaunch& g, hipStream_t stream);
 hipError_t launch_gemm_bf16(GemmLaunch& g, hipStream_t stream);

@@ -27,3 +27,18 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture
+def mecefo_option():
+    """Sets library switches (mecefo_set_option) for one test and puts them back to "auto" afterwards."""
+    from paper_2510_16415_amd import binding as B
+    changed = []
+
+    def set_option(name, value):
+        B.mecefo_set_option(name, value)
+        changed.append(name)
+
+    yield set_option
+    for name in changed:
+        B.mecefo_set_option(name, "auto")

@@ -78,6 +78,35 @@ def test_null_and_rank_validation_happens_before_any_launch():
     assert st == B.ERR_INVALID_ARG and "side" in B.mecefo_last_error()
 
 
+def test_partially_overlapping_dx_is_rejected():
+    """dX may be dOut or H themselves (in-place) or lie apart from them; a partial overlap would let the
+    Eq. (2) launches read rows of dOut that the norm backward has already overwritten."""
+    lib = B.lib()
+    d = B.make_desc(16, 64, 104, B.BF16)            # [16 x 64] bf16 = 2048 bytes
+    P = B.Proj(0x1000, 8, 8)
+    fake = C.c_void_p(0x100000)
+    dOut, H = C.c_void_p(0x200000), C.c_void_p(0x300000)
+    for dX, other in ((0x200000 + 1024, "dOut"), (0x200000 - 2032, "dOut"), (0x300000 + 16, "H")):
+        st = lib.mecefo_block_bwd_skip(C.byref(d), H, dOut, fake, fake, fake, fake, P, P, P, 0,
+                                       C.c_void_p(dX), fake, fake, fake, fake, 0, fake, 16, None)
+        assert st == B.ERR_INVALID_ARG and "overlaps " + other in B.mecefo_last_error(), B.mecefo_last_error()
+    # equal pointers and disjoint ranges pass the alias check (and then fail on the 16-byte workspace)
+    for dX in (0x200000, 0x300000, 0x200000 + 2048, 0x200000 - 2048):
+        st = lib.mecefo_block_bwd_skip(C.byref(d), H, dOut, fake, fake, fake, fake, P, P, P, 0,
+                                       C.c_void_p(dX), fake, fake, fake, fake, 0, fake, 16, None)
+        assert st == B.ERR_WORKSPACE_TOO_SMALL, B.mecefo_last_error()
+
+
+def test_set_option_validates_names_and_values():
+    B.mecefo_set_option("tile", "L8")
+    B.mecefo_set_option("tile", "auto")
+    B.mecefo_set_option("attention", "gemm")
+    B.mecefo_set_option("attention", "auto")
+    for name, value in (("tile", "L"), ("tile", "L9"), ("attention", "fast"), ("speed", "max")):
+        e = _err(B.mecefo_set_option, name, value)
+        assert e.status == B.ERR_INVALID_ARG
+
+
 def test_full_block_descriptor_and_pointer_validation():
     lib = B.lib()
     d = B.make_desc(32, 64, 104, B.BF16)
@@ -170,15 +199,14 @@ def test_stage_names_follow_the_header_enum():
     assert names == B.STAGES and int(count) == len(B.STAGES)
 
 
-def test_forward_workspace_has_no_score_buffer_when_the_attention_is_fused(monkeypatch):
+def test_forward_workspace_has_no_score_buffer_when_the_attention_is_fused(mecefo_option):
     """bf16 with head dimension 64 or 128 runs the fused attention forward: the workspace is a handful
-    of activations.  MECEFO_ATTN=gemm (or another head dimension) adds fp32 scores and probabilities."""
+    of activations.  the "attention" = "gemm" switch (or another head dimension) adds fp32 scores and probabilities."""
     b, d, f, seq, batch = 8192, 4096, 11008, 2048, 4
     desc = B.make_desc(b, d, f, B.BF16)
-    monkeypatch.delenv("MECEFO_ATTN", raising=False)
     fused = B.mecefo_block_fwd_workspace_bytes(desc, B.make_attn_desc(batch, seq, 32, d))       # dh = 128
     other = B.mecefo_block_fwd_workspace_bytes(desc, B.make_attn_desc(batch, seq, 16, d))       # dh = 256
-    monkeypatch.setenv("MECEFO_ATTN", "gemm")
+    mecefo_option("attention", "gemm")
     forced = B.mecefo_block_fwd_workspace_bytes(desc, B.make_attn_desc(batch, seq, 32, d))
     act = b * d * 2
     assert 6 * act <= fused <= 6 * act + b * f * 2 + (16 << 20)

@@ -61,8 +61,8 @@ def test_block_fwd_bf16_ragged(batch, seq, d, f, heads, pad):
 
 
 @pytest.mark.parametrize("tile", ["S", "L8R", "L8"])
-def test_block_fwd_bf16_forced_tiles_cross_the_diagonal(tile, monkeypatch):
-    monkeypatch.setenv("MECEFO_TILE", tile)
+def test_block_fwd_bf16_forced_tiles_cross_the_diagonal(tile, mecefo_option):
+    mecefo_option("tile", tile)
     print(tile, run_fwd(23, 2, 523, 256, 344, 2, "bf16")[-1])
     print(tile, run_fwd(24, 1, 768, 256, 344, 4, "bf16")[-1])
 
@@ -76,10 +76,10 @@ def test_block_fwd_bf16_fused_attention_shapes(batch, seq, d, heads, pad):
 
 
 @pytest.mark.parametrize("batch,seq,d,heads", [(2, 523, 256, 2), (1, 768, 256, 4)])
-def test_block_fwd_bf16_materialised_scores_path(batch, seq, d, heads, monkeypatch):
-    """MECEFO_ATTN=gemm keeps the chunked fp32-score form (the one other head dimensions use) covered
+def test_block_fwd_bf16_materialised_scores_path(batch, seq, d, heads, mecefo_option):
+    """the "attention" = "gemm" switch keeps the chunked fp32-score form (the one other head dimensions use) covered
     at head dimensions 128 and 64."""
-    monkeypatch.setenv("MECEFO_ATTN", "gemm")
+    mecefo_option("attention", "gemm")
     print(run_fwd(30, batch, seq, d, 344, heads, "bf16")[-1])
 
 

@@ -110,26 +110,26 @@ def test_full_block_bf16_ragged(batch, seq, d, f, heads):
 
 
 @pytest.mark.parametrize("tile", ["S", "L4", "L8R", "L8"])
-def test_full_block_bf16_forced_tiles_cross_the_diagonal(tile, monkeypatch):
+def test_full_block_bf16_forced_tiles_cross_the_diagonal(tile, mecefo_option):
     """Sequences longer than two tiles of every configuration, so that the causal clipping of the
     K loops and the skipped tiles above the diagonal are exercised; seq is not a multiple of 8."""
-    monkeypatch.setenv("MECEFO_TILE", tile)
+    mecefo_option("tile", tile)
     _, _, errs = run_case(3, 2, 523, 256, 344, 2, "bf16")
     print(tile, errs)
 
 
-def test_full_block_bf16_aligned_seq_large_tiles(monkeypatch):
+def test_full_block_bf16_aligned_seq_large_tiles(mecefo_option):
     """seq % 8 == 0 keeps every attention product on the direct-to-LDS kernel."""
-    monkeypatch.setenv("MECEFO_TILE", "L8")
+    mecefo_option("tile", "L8")
     _, _, errs = run_case(4, 2, 768, 256, 344, 4, "bf16", pad=8)
     print(errs)
 
 
 @pytest.mark.parametrize("batch,seq,d,heads", [(2, 523, 256, 2), (1, 768, 256, 4), (2, 130, 128, 2)])
-def test_full_block_bf16_five_product_attention_path(batch, seq, d, heads, monkeypatch):
-    """Head dimensions 64 and 128 normally take the fused dK / dV kernel; MECEFO_ATTN=gemm keeps the
+def test_full_block_bf16_five_product_attention_path(batch, seq, d, heads, mecefo_option):
+    """Head dimensions 64 and 128 normally take the fused dK / dV kernel; the "attention" = "gemm" switch keeps the
     five batched products (the path every other head dimension and the fp32 configuration use)."""
-    monkeypatch.setenv("MECEFO_ATTN", "gemm")
+    mecefo_option("attention", "gemm")
     _, _, errs = run_case(9, batch, seq, d, 344, heads, "bf16")
     print(errs)
 

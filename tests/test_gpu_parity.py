@@ -103,11 +103,11 @@ def test_norm_kernels_over_row_lengths(d, alias):
 
 @pytest.mark.parametrize("tile", ["S", "L4", "L8R", "L8"])
 @pytest.mark.parametrize("shape", [(300, 264, 333, 40), (513, 512, 1000, 129), (700, 520, 1365, 264)])
-def test_every_tile_configuration_on_ragged_shapes(shape, tile, monkeypatch):
+def test_every_tile_configuration_on_ragged_shapes(shape, tile, mecefo_option):
     """The launcher picks the tile configuration from the problem size; force each one (128x128
     and 256x256 register-staged tiles, 4 and 8 waves, and the direct-to-LDS kernel) onto shapes
     that are ragged against every tile edge, with an odd d_ff and ranks that are not multiples of 8."""
-    monkeypatch.setenv("MECEFO_TILE", tile)
+    mecefo_option("tile", tile)
     b, d, f, r = shape
     c = make_case(300 + b, b, d, f, r, "bf16")
     lay = Layer(b, d, f, "bf16", c["Wg"], c["Wu"], c["Wd"], c["gamma"], c["Pg"], c["Pu"], c["Pd"], EPS, pad_w=8)
