@@ -115,18 +115,26 @@ def token_ids(rng: np.random.Generator, batch: int, seq: int) -> np.ndarray:
 
 
 def stack_params(cfg: Config, layers: int | None = None):
-    """Embedding, per-layer MHA+FFN weights, final gain and untied LM head of a stack config."""
+    """Embedding, per-layer MHA+FFN weights, final gain and untied LM head of a stack config.
+
+    Every layer draws from a generator of its own (seeded by config and layer index), so the layers of
+    a deep stack can be drawn by several host threads and a layer's values do not depend on the depth."""
+    from concurrent.futures import ThreadPoolExecutor
+    import os
     L = cfg.layers if layers is None else layers
     d, f = cfg.d_model, cfg.d_ff
     rng = rng_for(cfg.index, 1)
     emb = _cast(_normal(rng, (VOCAB, d), 0.02), cfg.dtype)
     lm_head = _cast(_normal(rng, (VOCAB, d), 0.02), cfg.dtype)
-    blocks = []
-    for _ in range(L):
-        Wq, Wk, Wv, Wo, g_attn = mha_weights(rng, d, cfg.dtype)
-        Wg, Wu, Wd, g_ffn = ffn_weights(rng, d, f, cfg.dtype)
-        blocks.append(dict(Wq=Wq, Wk=Wk, Wv=Wv, Wo=Wo, g_attn=g_attn,
-                           Wg=Wg, Wu=Wu, Wd=Wd, g_ffn=g_ffn))
+
+    def draw(layer: int):
+        r = rng_for(cfg.index, 1, layer + 1)
+        Wq, Wk, Wv, Wo, g_attn = mha_weights(r, d, cfg.dtype)
+        Wg, Wu, Wd, g_ffn = ffn_weights(r, d, f, cfg.dtype)
+        return dict(Wq=Wq, Wk=Wk, Wv=Wv, Wo=Wo, g_attn=g_attn, Wg=Wg, Wu=Wu, Wd=Wd, g_ffn=g_ffn)
+
+    with ThreadPoolExecutor(max_workers=max(1, min(16, os.cpu_count() or 1, L))) as ex:
+        blocks = list(ex.map(draw, range(L)))
     return dict(emb=emb, lm_head=lm_head, g_final=np.ones(d, dtype=np.float32), blocks=blocks)
 
 

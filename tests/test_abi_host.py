@@ -97,6 +97,31 @@ def test_partially_overlapping_dx_is_rejected():
         assert st == B.ERR_WORKSPACE_TOO_SMALL, B.mecefo_last_error()
 
 
+def test_localised_gate_sees_one_wrong_column_of_a_large_matrix():
+    """The Frobenius ratio of a 2048 x 5461 matrix moves by 1/sqrt(5461) when one column is wrong, which is
+    below the 2e-2 gate; the per-row / per-column measure of the GPU parity tests reads order one."""
+    import numpy as np
+    from gpu_util import assert_close, local_relerr, relerr
+    rng = np.random.default_rng(5)
+    want = rng.standard_normal((2048, 5461))
+    good = want * (1 + 3e-3 * rng.standard_normal(want.shape))
+    assert_close({"dWd": good}, {"dWd": want}, 2e-2)
+    wrong_col = good.copy(); wrong_col[:, 5460] = 0.0                       # ragged last column lost
+    wrong_row = good.copy(); wrong_row[2047, :] *= 1.1                      # last row scaled
+    wrong_tile = good.copy(); wrong_tile[2016:, 5376:] = 0.0                # one wave's last 32 x 85 piece not written
+    for name, m in (("col", wrong_col), ("row", wrong_row), ("tile", wrong_tile)):
+        assert relerr(m, want) < 2e-2, name                                 # the global gate alone would pass
+        loc = local_relerr(m, want)
+        assert max(loc.values()) > 5e-2, (name, loc)
+        with pytest.raises(AssertionError):
+            assert_close({"dWd": m}, {"dWd": want}, 2e-2)
+    v = rng.standard_normal(4096)
+    assert local_relerr(v * (1 + 1e-3), v)["block"] < 2e-3
+    lost = v.copy(); lost[4032:] = 0.0                                      # the last 64 columns of a gain gradient
+    assert relerr(lost, v) > 2e-2 or local_relerr(lost, v)["block"] > 0.5
+    assert local_relerr(lost, v)["block"] > 0.5
+
+
 def test_set_option_validates_names_and_values():
     B.mecefo_set_option("tile", "L8")
     B.mecefo_set_option("tile", "auto")

@@ -179,9 +179,12 @@ def test_full_block_matches_skip_plus_attention_branch():
     _, H, _ = O.block_fwd_full(X, p, 4, 2, 64, EPS)
     skip = O.block_bwd_skip_exact_wgrad(H, dOut, p["g_ffn"], p["Wg"], p["Wu"], p["Wd"], EPS)
     for k in ("dWg", "dWu", "dWd"):
-        assert np.linalg.norm(got[k] - skip[k]) <= 1e-5 * np.linalg.norm(skip[k])
+        assert np.linalg.norm(got[k] - skip[k]) <= TOL["f32"] * np.linalg.norm(skip[k])
+    # The branch is a difference of two gradients that are each within the fp32 tolerance of their
+    # oracle values, so its own error is bounded by that tolerance times the norms that cancel.
     branch = got["dX"] - skip["dX"]
-    assert np.linalg.norm(branch - want["dX_branch"]) <= 1e-4 * np.linalg.norm(want["dX_branch"])
+    bound = TOL["f32"] * (np.linalg.norm(got["dX"]) + np.linalg.norm(skip["dX"]))
+    assert np.linalg.norm(branch - want["dX_branch"]) <= bound
 
 
 def test_config_c1_full_block():

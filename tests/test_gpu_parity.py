@@ -251,7 +251,7 @@ def test_full_rank_projection_reproduces_exact_gradient_on_gpu():
     lay = Layer(b, d, f, "f32", Wg, Wu, Wd, gamma, Pg, Pu, Pd, EPS)
     got = lay.block_bwd_skip(H, dOut)
     want = O.block_bwd_skip_exact_wgrad(H, dOut, gamma, Wg, Wu, Wd, EPS)
-    assert_close(got, want, 2e-5)
+    assert_close(got, want, TOL["f32"])
 
 
 def test_empty_batch_and_zero_gradient():
@@ -334,36 +334,39 @@ def test_config_c1_tiny_fp32_with_real_attention_forward():
     print("C1 errors", errs)
 
 
-def _stack_case(name, n_layers_checked, default_depth):
+def _stack_case(name, svd_layers=2):
     """Forward a token stack on the CPU (oracle harness) to get every stored H_l and the loss
-    gradient, then walk the degraded backward chain from the top, layer by layer, feeding the
-    GPU the oracle's dOut_l (teacher forcing) and comparing each layer's outputs.
+    gradient, then walk the degraded backward chain from the top through ALL layers of the config,
+    feeding the GPU the oracle's dOut_l (teacher forcing) and comparing each layer's outputs at the
+    stated tolerance.  The free-running chain (the GPU's own dX handed down) is printed, not gated.
 
-    Host time is dominated by drawing the weights and by the harness forward, neither of which
-    is under test, so by default the deep stacks are built with `default_depth` layers (every
-    layer at the config's full b, d, f, r); MECEFO_TEST_FULL_DEPTH=1 builds all of them."""
-    import dataclasses
-    import os
+    The projection is opaque data to the path: the top `svd_layers` layers take the paper's P (first r
+    right singular vectors of each FFN matrix, numpy SVD), the others an orthonormal Gaussian basis of
+    the same shape, which keeps the host time of a 24-layer stack within the GPU test budget."""
+    import time
+    t0 = time.time()
     cfg = I.CONFIGS[name]
-    depth = cfg.layers if os.environ.get("MECEFO_TEST_FULL_DEPTH") == "1" else min(cfg.layers, default_depth)
-    cfg = dataclasses.replace(cfg, layers=depth)
     params = I.stack_params(cfg)
     worst = {}
     chain_err = None
+    prng = I.rng_for(cfg.index, 9)
     for mb in range(cfg.micro_batches):
         ids = I.token_ids(I.rng_for(cfg.index, 2, mb), cfg.batch, cfg.seq)
         # The harness forward only manufactures realistic H_l / dOut; deep stacks run it in float32.
         hdt = np.float64 if cfg.layers <= 8 else np.float32
-        Hs, X_last = O.stack_forward(ids, params, cfg.heads, EPS, dtype=hdt, keep_last=n_layers_checked)
+        Hs, X_last = O.stack_forward(ids, params, cfg.heads, EPS, dtype=hdt, keep_last=cfg.layers)
         _, dOut = O.next_token_loss_grad(X_last, params, ids, EPS)
         dO_gpu = None
-        for li in range(cfg.layers - 1, cfg.layers - 1 - n_layers_checked, -1):
+        for li in range(cfg.layers - 1, -1, -1):
             p = params["blocks"][li]
             H = I.round_to_bf16_grid(Hs[li].astype(np.float32))
             dO = I.round_to_bf16_grid(dOut.astype(np.float32))
             key = (name, li)
             if key not in _LAYERS:
-                Ps = _svd_projections(p, cfg.rank, cfg.dtype)
+                if li >= cfg.layers - svd_layers:
+                    Ps = _svd_projections(p, cfg.rank, cfg.dtype)
+                else:
+                    Ps = tuple(I.random_orthonormal(prng, n, cfg.rank, cfg.dtype) for n in (cfg.d_model, cfg.d_model, cfg.d_ff))
                 _LAYERS[key] = (Layer(cfg.tokens, cfg.d_model, cfg.d_ff, cfg.dtype, p["Wg"], p["Wu"], p["Wd"],
                                       p["g_ffn"], *Ps, EPS), Ps)
             lay, Ps = _LAYERS[key]
@@ -386,7 +389,10 @@ def _stack_case(name, n_layers_checked, default_depth):
                 chain_err = relerr(dX_gpu, want["dX"])
                 dO_gpu = I.round_to_bf16_grid(dX_gpu)
             dOut = want["dX"]
-    print(f"{name}: worst per-layer errors {worst}; free-running chain dX error {chain_err}")
+            if mb == cfg.micro_batches - 1:      # last use of this layer: release its device buffers
+                del _LAYERS[key], _ACC[key]
+    print(f"{name}: {cfg.layers} layers x {cfg.micro_batches} micro-batch(es) in {time.time() - t0:.0f} s; worst per-layer "
+          f"errors {worst}; free-running chain dX error after {cfg.layers} layers {chain_err}")
     _LAYERS.clear()
     _ACC.clear()
     torch.cuda.empty_cache()
@@ -409,16 +415,17 @@ def lay_free_run(lay, H, dOut):
 
 
 def test_config_c2_llama60m_stack_all_layers():
-    _stack_case("C2", I.CONFIGS["C2"].layers, 8)
+    _stack_case("C2", svd_layers=8)
 
 
 def test_config_c3_llama350m_stack_two_microbatches():
-    """Top layers of the 24-layer stack, own + absorbed micro-batch (second accumulates)."""
-    _stack_case("C3", 3, 4)
+    """All 24 layers, own + absorbed micro-batch (the second accumulates into the same gradient buffers)."""
+    _stack_case("C3")
 
 
 def test_config_c4_llama1b_stack_odd_dff():
-    _stack_case("C4", 2, 3)
+    """All 24 layers; d_ff = 5461 is odd (row stride 5464, ragged last tile column)."""
+    _stack_case("C4")
 
 
 def test_config_c5_llama7b_layer_full_size():
