@@ -7,9 +7,10 @@ backward + residual (the MHA skip) -- over one batch of synthetic input resident
 Workload: the LLaMA-7B-shaped layer (d=4096, f=11008, 4 x 2048 tokens, r=1024, bf16 storage,
 fp32 accumulation), the configuration the headline metric is quoted on.
 
-Prints ONE JSON line.  `value` = tokens/s through the layer.  `roofline` is for the dominant
-kernel stage, timed with HIP events on the launch stream inside the timed region;
-`cpu_baseline` is the fp64 numpy oracle timed on the host on a bounded token sample.
+Prints ONE JSON line.  `value` = tokens/s through the layer, from the timed region (K steps between two
+synchronisations, no per-stage events inside it).  Per-stage times, the `roofline` of the dominant kernel
+stage and the shader clock come from a second pass of the same K steps with a HIP-event pair (on the
+launch stream) around every stage.  `cpu_baseline` is the numpy oracle timed on the host.
 """
 import argparse
 import json
@@ -23,18 +24,20 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure (no sparsity)
 PEAK_HBM_GBS = 8000.0
+PEAK_F32_VECTOR_TFLOPS = 157.3   # fp32 path of config C1: plain vector FMA
 
-# HBM-side bytes per launch of the C5 GEMM stages: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (two
-# runs of this script), each divided by what the same counter reads for a plain 1 GiB device copy
-# (0.500 and 1.000).  Source and commands: profiles/gemm_bf16_C5_hbm_traffic.md.
-C5_TRAFFIC_BYTES = {
-    "dgrad_down": (1215 + 172) * 2**20,
-    "recompute": (2677 + 516) * 2**20,
-    "dgrad_gate_up": (2080 + 64) * 2**20,
-    "project": (761 + 48) * 2**20,
-    "contract": (1434 + 51) * 2**20,
-    "expand": (630 + 517) * 2**20,
-}
+def c5_traffic_bytes():
+    """HBM-side bytes per launch of the C5 GEMM stages from the two rocprofv3 --pmc runs of this script
+    (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB device copy):
+    the machine-readable block of profiles/gemm_bf16_C5_hbm_traffic.md, with the commit of the kernels it
+    was taken on.  None when the file has no such block."""
+    import re
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_C5_hbm_traffic.md")
+    try:
+        m = re.search(r"```json\s*(\{.*?\})\s*```", open(path).read(), re.S)
+        return json.loads(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def stage_flops(b, d, f, r):
@@ -54,11 +57,14 @@ def stage_flops(b, d, f, r):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C5", help="C5 (headline) or C2/C3/C4 single-layer shapes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overhead", action="store_true")
+    ap.add_argument("--data", default="gaussian", choices=["gaussian", "zeros"],
+                    help="zeros: every operand zero (same work, no switching in the matrix cores: shows how far "
+                         "the Gaussian workload is held back by the power limit)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -94,7 +100,8 @@ def main():
 
     def randn(rows, cols, std=1.0, ld=None):
         t = torch.zeros(rows, ld or cols, dtype=bf, device=dev)
-        t[:, :cols] = (torch.randn(rows, cols, generator=gen, device=dev) * std).to(bf)
+        if args.data == "gaussian":
+            t[:, :cols] = (torch.randn(rows, cols, generator=gen, device=dev) * std).to(bf)
         return t
 
     # Synthetic data with the workload's distributions: weights N(0, 0.02^2), stored FFN input and
@@ -117,18 +124,30 @@ def main():
         B.mecefo_block_bwd_skip(desc, H, dOut, gamma, Wg, Wu, Wd, *projs, B.SIDE_INPUT, dX, dgamma,
                                 dWg, dWu, dWd, 0, ws)
 
+    B.mecefo_init()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.mecefo_profile_enable(16 * args.steps)
+    # Timed region: exactly K steps between two synchronisations; one HIP-event pair around all of them.
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step_events = ev0.elapsed_time(ev1) / args.steps
+    # Second pass, outside the timed region: the same K steps with an event pair around every stage
+    # (and the shader-clock samples of the GEMM launches).
+    B.mecefo_profile_enable(16 * args.steps)
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
     stages = B.mecefo_profile_collect()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # per-step spread (outside the timed region): one event pair per step on the launch stream
+    clocks = B.mecefo_profile_clock_mhz()
+    # Third pass: per-step spread, one event pair per step on the launch stream
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for e0, e1 in ev:
         e0.record()
@@ -146,6 +165,8 @@ def main():
         e = {"ms": round(avg, 4)}
         if name in sf:
             e["tflops"] = round(sf[name] / (avg * 1e-3) / 1e12, 1)
+        if name in clocks:
+            e["shader_clock_mhz"] = round(clocks[name], 0)
         stage_report[name] = e
     gemm_stages = {k: v for k, v in stage_report.items() if "tflops" in v}
     dom = max(gemm_stages, key=lambda k: gemm_stages[k]["ms"])
@@ -158,6 +179,8 @@ def main():
     if "norm_bwd" in stage_report:
         hbm["norm_bwd_GBs"] = round(4 * b * d * 2 / (stage_report["norm_bwd"]["ms"] * 1e-3) / 1e9, 1)
 
+    traffic = c5_traffic_bytes() if cfg.name == "C5" else None
+    dom_clock = clocks.get(dom)
     out = {
         "metric": "degraded-block bwd tokens/sec",
         "value": round(tokens_per_s, 1),
@@ -175,6 +198,7 @@ def main():
                                "bf16 storage / fp32 accumulate, SIDE_INPUT projections"
                    if cfg.name == "C5" else f"{cfg.name}: one layer d={d} f={f} tokens={b} r={r}",
                    "tokens": b, "d_model": d, "d_ff": f, "rank": r},
+        "ms_per_step_events": round(ms_per_step_events, 4),
         "ms_per_step_median": round(per_step[len(per_step) // 2], 4),
         "ms_per_step_min": round(per_step[0], 4),
         "tflops_per_layer": round(flops_layer / (ms_per_step * 1e-3) / 1e12, 1),
@@ -183,8 +207,14 @@ def main():
         "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_dtl_kernel, launch '{dom}'",
                      "achieved": round(dom_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": C5_TRAFFIC_BYTES.get(dom) if cfg.name == "C5" else None,
-                     "flops_per_launch": sf[dom], "ms_per_launch": gemm_stages[dom]["ms"]},
+                     "traffic": (traffic or {}).get("bytes_per_launch", {}).get(dom),
+                     "traffic_source": ("profiles/gemm_bf16_C5_hbm_traffic.md, kernels of commit "
+                                        + str(traffic.get("commit"))) if traffic else None,
+                     "flops_per_launch": sf[dom], "ms_per_launch": gemm_stages[dom]["ms"],
+                     "shader_clock_mhz": round(dom_clock, 0) if dom_clock else None,
+                     "peak_at_that_clock": round(PEAK_BF16_TFLOPS * dom_clock / 2400.0, 1) if dom_clock else None,
+                     "timing": "HIP events on the launch stream, second pass of the same K steps"},
+        "data_values": args.data,
         "stages": stage_report,
         "hbm_bound_kernels": hbm,
     }
@@ -199,6 +229,7 @@ def main():
                                    dgamma, dWg, dWu, dWd)
         out["neighbor_stack"] = neighbor_stack(B, torch, I)
         out["step_compositions_per_layer"] = step_compositions(B, torch, I)
+        out["per_config_one_layer"] = per_config_lines(B, torch, I)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
@@ -511,16 +542,18 @@ def step_compositions(B, torch, I, names=("C3", "C4")):
 
 
 def cpu_baseline(cfg):
-    """The fp64 numpy oracle, as it stands, timed on whole passes over the batch of the same layer
-    until about ten seconds of host time have gone by."""
+    """The numpy oracle, as it stands, timed on the host cores on the same layer.  `value` is its fp64 form
+    (the one the parity tests compare against) over whole passes of the batch; `legs` adds its float32 form
+    (numpy BLAS sgemm) on all cores over the whole batch and on one thread over a bounded token sample."""
     import numpy as np
 
     from oracle import mecefo_oracle as O
     from paper_2510_16415_amd import inputs as I
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
+        threadpool_limits = None
         threads = os.cpu_count()
     bs = cfg.tokens
     d, f, r = cfg.d_model, cfg.d_ff, cfg.rank
@@ -528,16 +561,90 @@ def cpu_baseline(cfg):
     Wg, Wu, Wd, gamma = I.ffn_weights(rng, d, f, cfg.dtype)
     H, dOut = I.gaussian_block_io(rng, bs, d, cfg.dtype)
     Ps = [I._normal(rng, (n, r), n ** -0.5) for n in (d, d, f)]
-    t = time.perf_counter()
-    passes = 0
-    while True:      # whole passes over the batch until about ten seconds of host work are on the clock
-        O.block_bwd_skip(H, dOut, gamma, Wg, Wu, Wd, *Ps, 1e-6)
-        passes += 1
-        dt = time.perf_counter() - t
-        if dt >= 10.0 or passes >= 8:
-            break
-    return {"value": round(passes * bs / dt, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{passes} passes over the {bs} tokens of the same layer, fp64 numpy, {dt:.1f} s"}
+
+    def run(tokens, dtype, budget_s, max_passes):
+        t = time.perf_counter()
+        passes = 0
+        while True:
+            O.block_bwd_skip(H[:tokens], dOut[:tokens], gamma, Wg, Wu, Wd, *Ps, 1e-6, dtype=dtype)
+            passes += 1
+            dt = time.perf_counter() - t
+            if dt >= budget_s or passes >= max_passes:
+                return passes, dt
+
+    passes, dt = run(bs, np.float64, 8.0, 6)
+    out = {"value": round(passes * bs / dt, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"{passes} passes over the {bs} tokens of the same layer, fp64 numpy, {dt:.1f} s"}
+    legs = {}
+    p32, dt32 = run(bs, np.float32, 5.0, 6)
+    legs["fp32_all_cores"] = {"value": round(p32 * bs / dt32, 1), "unit": "tokens/s", "cores": int(threads),
+                              "sample": f"{p32} passes over {bs} tokens, float32 numpy, {dt32:.1f} s"}
+    if threadpool_limits is not None:
+        sample = max(1, min(bs, 512))
+        with threadpool_limits(limits=1):
+            p1, dt1 = run(sample, np.float32, 6.0, 2)
+        legs["fp32_one_thread"] = {"value": round(p1 * sample / dt1, 1), "unit": "tokens/s", "cores": 1,
+                                   "sample": f"{p1} pass(es) over the first {sample} tokens (the token-independent "
+                                             f"expand products of Eq. (2) included once per pass), float32 numpy, {dt1:.1f} s"}
+    out["legs"] = legs
+    return out
+
+
+def per_config_lines(B, torch, I, names=("C1", "C2", "C3", "C4")):
+    """Degraded-block backward of ONE layer of each smaller config (parity configs, launch- and
+    occupancy-bound): tokens/s, algorithmic TFLOP/s and fraction of the peak of the arithmetic type."""
+    dev = torch.device("cuda:0")
+    out = {}
+    for name in names:
+        cfg = I.CONFIGS[name]
+        b, d, f, r = cfg.tokens, cfg.d_model, cfg.d_ff, cfg.rank
+        bf16 = cfg.dtype == "bf16"
+        t = torch.bfloat16 if bf16 else torch.float32
+        ldf = (f + 7) // 8 * 8 if bf16 else f
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(999 + cfg.index)
+
+        def rn(rows, cols, std=1.0, ld=None):
+            x = torch.zeros(rows, ld or cols, dtype=t, device=dev)
+            x[:, :cols] = (torch.randn(rows, cols, generator=gen, device=dev) * std).to(t)
+            return x
+
+        desc = B.make_desc(b, d, f, B.BF16 if bf16 else B.F32, B.F32, d, ldf, d, ldf)
+        Wg, Wu, Wd = rn(f, d, 0.02), rn(f, d, 0.02), rn(d, f, 0.02, ldf)
+        H, dOut = rn(b, d), rn(b, d)
+        gamma = torch.ones(d, dtype=t, device=dev)
+        rr = (r + 7) // 8 * 8 if bf16 else r
+        Ps = [rn(d, r, d ** -0.5, rr), rn(d, r, d ** -0.5, rr), rn(f, r, f ** -0.5, rr)]
+        projs = [B.proj(P, r) for P in Ps]
+        ws = torch.empty(B.mecefo_workspace_bytes(desc, r, r, r), dtype=torch.uint8, device=dev)
+        dX = torch.empty_like(dOut)
+        g = [torch.zeros(f, d, device=dev), torch.zeros(f, d, device=dev), torch.zeros(d, ldf, device=dev),
+             torch.zeros(d, device=dev)]
+
+        def step():
+            B.mecefo_block_bwd_skip(desc, H, dOut, gamma, Wg, Wu, Wd, *projs, B.SIDE_INPUT, dX, g[3], g[0], g[1],
+                                    g[2], 0, ws)
+
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        for e0, e1 in ev:
+            e0.record()
+            step()
+            e1.record()
+        torch.cuda.synchronize()
+        ts = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+        ms = ts[len(ts) // 2]
+        flops = b * (10 * d * f + 6 * r * (d + f)) + 6 * r * d * f
+        peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_VECTOR_TFLOPS
+        out[name] = {"layer": f"tokens={b}, d={d}, f={f}, r={r}, {cfg.dtype}" + (" (plain FMA path, untuned)" if not bf16 else ""),
+                     "ms_per_layer_median": round(ms, 4), "ms_per_layer_min": round(ts[0], 4),
+                     "tokens_per_s": round(b / (ms * 1e-3), 1),
+                     "tflops_per_layer": round(flops / (ms * 1e-3) / 1e12, 2),
+                     "frac_of_peak": round(flops / (ms * 1e-3) / 1e12 / peak, 4),
+                     "peak_tflops": peak}
+    return out
 
 
 if __name__ == "__main__":

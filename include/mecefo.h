@@ -301,7 +301,11 @@ mecefo_status_t mecefo_block_bwd_skip_ex(const mecefo_ffn_desc_t* desc, const vo
  * by a pair of HIP events on the call's own stream, for at most n stage launches.
  * mecefo_profile_collect() waits for them, adds elapsed milliseconds and launch counts per
  * stage into two arrays of MECEFO_STAGE_COUNT entries, and switches timing off again.
- * Not thread-safe; meant for benchmarks. */
+ * While timing is on, the bf16 direct-to-LDS GEMM launches also sample the shader clock (every 64th
+ * workgroup stores the core-clock cycles and the constant-rate 100 MHz ticks it ran for);
+ * mecefo_profile_clock_mhz() returns, after a collect, the average clock in MHz per stage (0 where no
+ * such launch ran).  These calls allocate and free a small device buffer and HIP events, are not
+ * thread-safe and keep process-wide state: they are meant for benchmarks, one host thread at a time. */
 typedef enum {
   MECEFO_STAGE_NORM_FWD = 0,       /* RMSNorm recompute from the stored tensor               */
   MECEFO_STAGE_DGRAD_DOWN = 1,     /* dA = dY Wd                                             */
@@ -329,6 +333,7 @@ typedef enum {
 } mecefo_stage_t;
 mecefo_status_t mecefo_profile_enable(int max_stage_launches);
 mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_stage);
+mecefo_status_t mecefo_profile_clock_mhz(double* mhz_by_stage);
 
 /* Prepares the current device: raises the dynamic-LDS limit of every kernel that needs more than the
  * default (what the first launch of each kernel would otherwise do on the host).  Optional; for callers

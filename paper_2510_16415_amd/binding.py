@@ -123,6 +123,8 @@ def lib() -> C.CDLL:
     L.mecefo_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
     L.mecefo_profile_enable.restype = C.c_int
     L.mecefo_profile_collect.restype = C.c_int
+    L.mecefo_profile_clock_mhz.argtypes = [C.POINTER(C.c_double)]
+    L.mecefo_profile_clock_mhz.restype = C.c_int
     L.mecefo_init.argtypes = []
     L.mecefo_init.restype = C.c_int
     L.mecefo_set_option.argtypes = [C.c_char_p, C.c_char_p]
@@ -339,6 +341,14 @@ def mecefo_profile_collect():
     cnt = (C.c_int * n)()
     _check(lib().mecefo_profile_collect(ms, cnt))
     return {STAGES[i]: (ms[i], cnt[i]) for i in range(n) if cnt[i]}
+
+
+def mecefo_profile_clock_mhz():
+    """After mecefo_profile_collect: {stage name: average shader clock in MHz} of the sampled GEMM launches."""
+    n = len(STAGES)
+    mhz = (C.c_double * n)()
+    _check(lib().mecefo_profile_clock_mhz(mhz))
+    return {STAGES[i]: mhz[i] for i in range(n) if mhz[i] > 0}
 
 
 def mecefo_init():

@@ -126,11 +126,15 @@ mecefo_status_t check_proj(const Ctx& c, const mecefo_proj_t& P, int dim, const 
 #define HIP_TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return fail(MECEFO_ERR_LAUNCH, "%s: %s", #x, hipGetErrorString(e__)); } while (0)
 
 // ---- optional per-stage timing (measurement only) --------------------------------------
+constexpr int kClkPairs = 64;      // (cycles, wall ticks) pairs per stage launch
 struct Profiler {
   bool on = false;
   std::vector<hipEvent_t> ev;     // pairs (start, stop)
   std::vector<int> stage;
   size_t used = 0;                // events used
+  uint32_t* clk = nullptr;        // device: [stage launches][kClkPairs][2], zero-filled by mecefo_profile_enable
+  uint32_t* cur_clk = nullptr;    // slot of the stage that is being enqueued
+  double mhz[MECEFO_STAGE_COUNT] = {};
 } g_prof;
 
 struct StageTimer {
@@ -140,6 +144,7 @@ struct StageTimer {
     if (g_prof.on && g_prof.used + 2 <= g_prof.ev.size()) {
       active = true;
       g_prof.stage[g_prof.used / 2] = stage;
+      g_prof.cur_clk = g_prof.clk ? g_prof.clk + (g_prof.used / 2) * kClkPairs * 2 : nullptr;
       (void)hipEventRecord(g_prof.ev[g_prof.used], s);
     }
   }
@@ -147,6 +152,7 @@ struct StageTimer {
     if (active) {
       (void)hipEventRecord(g_prof.ev[g_prof.used + 1], s);
       g_prof.used += 2;
+      g_prof.cur_clk = nullptr;
     }
   }
 };
@@ -281,6 +287,7 @@ GemmLaunch new_launch(const Ctx& c, bool akc, bool bkc, int epi) {
   g.bf16 = c.bf16;
   g.out_f32 = c.grad_f32;
   g.splits = 1;
+  g.clk = g_prof.cur_clk;
   return g;
 }
 
@@ -435,6 +442,7 @@ mecefo_status_t lowrank_wgrad(const Ctx& c, const Bufs& bf, const void* U, int64
     }
     {
       STAGE(MECEFO_STAGE_CONTRACT, s);
+      g.clk = g_prof.cur_clk;
       HIP_TRY(launch_gemm(g, s));
     }
     if (splits > 1) {
@@ -608,15 +616,26 @@ mecefo_status_t mecefo_profile_enable(int max_launches) {
   g_prof.ev.assign((size_t)max_launches * 2, nullptr);
   g_prof.stage.assign((size_t)max_launches, 0);
   for (auto& e : g_prof.ev) HIP_TRY(hipEventCreate(&e));
+  if (g_prof.clk) { (void)hipFree(g_prof.clk); g_prof.clk = nullptr; }
+  const size_t clk_bytes = (size_t)max_launches * kClkPairs * 2 * sizeof(uint32_t);
+  HIP_TRY(hipMalloc((void**)&g_prof.clk, clk_bytes));
+  HIP_TRY(hipMemset(g_prof.clk, 0, clk_bytes));
   g_prof.used = 0;
   g_prof.on = true;
   return MECEFO_OK;
 }
 
+mecefo_status_t mecefo_profile_clock_mhz(double* mhz_by_stage) {
+  if (!mhz_by_stage) return fail(MECEFO_ERR_INVALID_ARG, "output array is NULL");
+  for (int i = 0; i < MECEFO_STAGE_COUNT; ++i) mhz_by_stage[i] = g_prof.mhz[i];
+  return MECEFO_OK;
+}
+
 mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_stage) {
   if (!ms_by_stage || !launches_by_stage) return fail(MECEFO_ERR_INVALID_ARG, "output arrays are NULL");
-  for (int i = 0; i < MECEFO_STAGE_COUNT; ++i) { ms_by_stage[i] = 0.0; launches_by_stage[i] = 0; }
+  for (int i = 0; i < MECEFO_STAGE_COUNT; ++i) { ms_by_stage[i] = 0.0; launches_by_stage[i] = 0; g_prof.mhz[i] = 0.0; }
   g_prof.on = false;
+  g_prof.cur_clk = nullptr;
   for (size_t i = 0; i + 1 < g_prof.used; i += 2) {
     HIP_TRY(hipEventSynchronize(g_prof.ev[i + 1]));
     float ms = 0.f;
@@ -625,6 +644,19 @@ mecefo_status_t mecefo_profile_collect(double* ms_by_stage, int* launches_by_sta
     ms_by_stage[st] += ms;
     launches_by_stage[st] += 1;
   }
+  if (g_prof.clk && g_prof.used >= 2) {   // shader clock per stage: cycles / wall ticks (100 MHz) of the sampled workgroups
+    const size_t launches = g_prof.used / 2;
+    std::vector<uint32_t> h(launches * kClkPairs * 2);
+    HIP_TRY(hipMemcpy(h.data(), g_prof.clk, h.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    double cyc[MECEFO_STAGE_COUNT] = {}, ticks[MECEFO_STAGE_COUNT] = {};
+    for (size_t l = 0; l < launches; ++l)
+      for (int k = 0; k < kClkPairs; ++k) {
+        const uint32_t c = h[(l * kClkPairs + k) * 2], w = h[(l * kClkPairs + k) * 2 + 1];
+        if (c && w) { cyc[g_prof.stage[l]] += c; ticks[g_prof.stage[l]] += w; }
+      }
+    for (int i = 0; i < MECEFO_STAGE_COUNT; ++i) g_prof.mhz[i] = ticks[i] > 0 ? 100.0 * cyc[i] / ticks[i] : 0.0;
+  }
+  if (g_prof.clk) { (void)hipFree(g_prof.clk); g_prof.clk = nullptr; }
   for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
   g_prof.ev.clear();
   g_prof.stage.clear();

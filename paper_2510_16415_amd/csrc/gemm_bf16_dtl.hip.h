@@ -222,6 +222,9 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
   const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
 
   const int nblocks = args.total_tiles * args.splits;
+  // Measurement only: shader-clock cycles and constant-rate (100 MHz) ticks this workgroup takes.
+  uint64_t clk_c0 = 0, clk_w0 = 0;
+  if (args.clk) { clk_c0 = clock64(); clk_w0 = wall_clock64(); }
   const TileCoord tc = map_tile(args, xcd_remap(blockIdx.x, nblocks));
   const GemmProblem p = product_view<2>(args.p[tc.prob], tc.z);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN_OUT;
@@ -396,6 +399,11 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
         epilogue_vec8<EPI>(p, args, tc.prob, tc.split, row_w + i * 32 + rl, col_w, v, v2);
       }
     }
+  }
+  if (args.clk && (blockIdx.x & 63) == 0 && t == 0) {
+    uint32_t* o = args.clk + 2 * ((blockIdx.x >> 6) & 63);
+    o[0] = (uint32_t)(clock64() - clk_c0);
+    o[1] = (uint32_t)(wall_clock64() - clk_w0);
   }
 }
 

@@ -102,6 +102,7 @@ hipError_t run_bf16(GemmLaunch& g, hipStream_t stream) {
   a.out_f32 = g.out_f32;
   a.partial = g.partial;
   a.krot = 8;
+  a.clk = g.clk;
   if (tiles == 0) return hipSuccess;
   const hipError_t e = Kern::prepare();
   if (e != hipSuccess) return e;

@@ -15,6 +15,8 @@ struct KArgs {
   float* partial;
   int64_t partial_off[3];
   int krot;          // direct-to-LDS kernel: tile row tm starts its K loop at stage tm % krot (0: off)
+  uint32_t* clk;     // measurement (NULL otherwise): every 64th workgroup stores its shader-clock cycles and
+                     // its 100 MHz wall ticks, pair number (workgroup / 64) % 64
   // Schedule (filled by fill_schedule): the logical tile order is eight consecutive segments, one
   // per XCD; segment x lists, heaviest problem first, the x-th eighth of every problem's tiles.
   int order[3];         // problem indices, most work per tile first

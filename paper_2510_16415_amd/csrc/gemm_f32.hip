@@ -93,6 +93,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const KArgs args, int a_k
 template <int EPI>
 hipError_t run_f32(GemmLaunch& g, hipStream_t stream) {
   KArgs a;
+  a.clk = nullptr;
   a.nprob = g.nprob;
   int tiles = 0;
   for (int i = 0; i < 3; ++i) {

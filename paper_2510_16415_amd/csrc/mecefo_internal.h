@@ -62,6 +62,7 @@ struct GemmLaunch {
   float* partial;   // EPI_SPLIT_F32: base of the partial buffer; problem i starts at partial_off[i]
   int64_t partial_off[3];
   bool force_large; // bf16: use the 256 x 256 direct-to-LDS configuration even for few tiles (split launches)
+  uint32_t* clk;    // measurement: 64 (cycles, wall ticks) pairs written by the direct-to-LDS kernel, or NULL
 };
 
 // Records the thread-local error text returned by mecefo_last_error() and returns `status`.
