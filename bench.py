@@ -179,6 +179,23 @@ def main():
     if "norm_bwd" in stage_report:
         hbm["norm_bwd_GBs"] = round(4 * b * d * 2 / (stage_report["norm_bwd"]["ms"] * 1e-3) / 1e9, 1)
 
+    # What a plain device copy of tensors of this size reaches on this machine (rotating buffers, HIP events):
+    # the practical ceiling for the two norm kernels, whose tensors are 64 MiB at C5.
+    nb = b * d * 2
+    srcs = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(6)]
+    dsts = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(6)]
+    for s_, d_ in zip(srcs, dsts):
+        d_.copy_(s_)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for i in range(24):
+        dsts[i % 6].copy_(srcs[i % 6])
+    c1.record()
+    torch.cuda.synchronize()
+    hbm["plain_copy_same_size_GBs"] = round(2 * nb / (c0.elapsed_time(c1) / 24 * 1e-3) / 1e9, 1)
+    hbm["note"] = ("norm kernels timed inside the step (norm_fwd directly behind the previous step's 516 MB of "
+                   "gradient stores); plain_copy: torch device copy of one [tokens x d_model] tensor, back to back")
+    del srcs, dsts
     traffic = c5_traffic_bytes() if cfg.name == "C5" else None
     dom_clock = clocks.get(dom)
     out = {
