@@ -232,6 +232,42 @@ mecefo_status_t mecefo_stack_bwd_skip(const mecefo_ffn_desc_t* desc, int n_layer
     mecefo_side_t side, const void* dOut_top, void* dX_bottom, int accumulate,
     void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- Mode per layer and the local step counters (Alg. 1: a node that takes over a failed peer's layers
+ * runs those layers in neighbor mode and sets their counters t_{i,l} to zero; Alg. 3: in neighbor mode
+ * the projection of layer l is recomputed from the current weights whenever t_{i,l} mod tau == 0, then
+ * recompute, Eq. (2) and the skip run, and t_{i,l} grows by one; Sec. 5, extension paragraph: the skip may
+ * be applied to a subset of the layers).  Counters are host integers owned by the caller. */
+typedef enum { MECEFO_MODE_STANDARD = 0, MECEFO_MODE_NEIGHBOR = 1 } mecefo_mode_t;
+
+typedef struct {
+  int64_t tau;                                     /* refresh period, >= 1 (the paper's runs: 100)          */
+  int32_t power_iters, cond_steps, polish_steps;   /* arguments of mecefo_projection_refresh (warm start)    */
+} mecefo_refresh_policy_t;
+
+/* 1 when a layer whose counter reads t must recompute its projection before this backward (t mod tau == 0). */
+int mecefo_refresh_due(int64_t t, int64_t tau);
+/* Alg. 1, on a failure: the counters of the layers taken over start again at zero (host memory). */
+void mecefo_counters_reset(int64_t* t, int n_layers);
+
+/* Backward of a stack whose layers run in the mode given per layer (host array modes[n_layers]), from the
+ * top layer down, each layer's dX handed to the layer below in dX_bottom's buffer (may alias dOut_top).
+ * in[l] / grads[l]: a standard-mode layer needs every field as mecefo_block_bwd_full does (dOut and dX are
+ * ignored: the chain supplies them); a neighbor-mode layer reads in[l].H, g_ffn, Wg, Wu, Wd only, takes
+ * its projections and FFN gradient buffers from lowrank[l], and leaves every MHA gradient buffer untouched.
+ * policy and t [n_layers] (both or neither): when given, a neighbor-mode layer with
+ * mecefo_refresh_due(t[l], policy->tau) first overwrites its three projections (device memory behind
+ * lowrank[l].Pg/Pu/Pd) with mecefo_projection_refresh of its weights, warm-started from their present
+ * contents, and t[l] is incremented after the layer's backward has been enqueued; standard-mode layers
+ * leave t[l] alone.  The refresh decision is taken on the host while enqueuing: a captured graph replays
+ * the decisions of the capture.  Workspace: mecefo_stack_mixed_workspace_bytes. */
+mecefo_status_t mecefo_stack_mixed_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+    int r_gate, int r_up, int r_down, size_t* out_bytes);
+mecefo_status_t mecefo_stack_bwd_mixed(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+    int n_layers, const mecefo_mode_t* modes, const mecefo_block_inputs_t* in,
+    const mecefo_block_grads_t* grads, const mecefo_layer_lowrank_t* lowrank, mecefo_side_t side,
+    const mecefo_refresh_policy_t* policy, int64_t* t, const void* dOut_top, void* dX_bottom,
+    int accumulate, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ---- After the backward pass of a layer (Alg. 1): gradient average and optimizer step.
  * mecefo_grad_average is Eq. (1) on gradient buffers that live on this GPU (the exchange between
  * ranks is not part of the library): out = mean over the ranks r with contributes[r] != 0 of

@@ -69,6 +69,13 @@ class LayerLowrank(C.Structure):
                 ("dWu", C.c_void_p), ("dWd", C.c_void_p)]
 
 
+class RefreshPolicy(C.Structure):
+    _fields_ = [("tau", C.c_int64), ("power_iters", C.c_int32), ("cond_steps", C.c_int32), ("polish_steps", C.c_int32)]
+
+
+MODE_STANDARD, MODE_NEIGHBOR = 0, 1
+
+
 class SkipOptions(C.Structure):
     _fields_ = [("G", C.c_void_p), ("Z", C.c_void_p), ("exact_wgrad_mask", C.c_int32)]
 
@@ -123,6 +130,17 @@ def lib() -> C.CDLL:
     L.mecefo_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
     L.mecefo_profile_enable.restype = C.c_int
     L.mecefo_profile_collect.restype = C.c_int
+    L.mecefo_refresh_due.argtypes = [C.c_int64, C.c_int64]
+    L.mecefo_refresh_due.restype = C.c_int
+    L.mecefo_counters_reset.argtypes = [C.POINTER(C.c_int64), C.c_int]
+    L.mecefo_counters_reset.restype = None
+    L.mecefo_stack_mixed_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    L.mecefo_stack_mixed_workspace_bytes.restype = C.c_int
+    L.mecefo_stack_bwd_mixed.argtypes = [D, C.POINTER(AttnDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(BlockInputs),
+                                         C.POINTER(BlockGrads), C.POINTER(LayerLowrank), C.c_int,
+                                         C.POINTER(RefreshPolicy), C.POINTER(C.c_int64), _vp, _vp, C.c_int, _vp,
+                                         C.c_size_t, _vp]
+    L.mecefo_stack_bwd_mixed.restype = C.c_int
     L.mecefo_profile_clock_mhz.argtypes = [C.POINTER(C.c_double)]
     L.mecefo_profile_clock_mhz.restype = C.c_int
     L.mecefo_init.argtypes = []
@@ -296,6 +314,36 @@ def mecefo_stack_bwd_skip(desc, layers, H, lowrank, side, dOut_top, dX_bottom, a
     p, n = _ws(ws)
     _check(lib().mecefo_stack_bwd_skip(C.byref(desc), len(layers), layers, _ptr_array(H), lowrank, int(side),
                                        _ptr(dOut_top), _ptr(dX_bottom), int(accumulate), p, n, _stream(stream)))
+
+
+def mecefo_refresh_due(t: int, tau: int) -> bool:
+    return bool(lib().mecefo_refresh_due(int(t), int(tau)))
+
+
+def mecefo_counters_reset(counters):
+    """counters: ctypes array of int64 (the per-layer step counters of one rank), set to zero in place."""
+    lib().mecefo_counters_reset(counters, len(counters))
+
+
+def mecefo_stack_mixed_workspace_bytes(desc, attn, r_gate=0, r_up=0, r_down=0) -> int:
+    out = C.c_size_t(0)
+    _check(lib().mecefo_stack_mixed_workspace_bytes(C.byref(desc), C.byref(attn), r_gate, r_up, r_down, C.byref(out)))
+    return out.value
+
+
+def mecefo_stack_bwd_mixed(desc, attn, modes, inputs, grads, lowrank, side, policy, counters, dOut_top, dX_bottom,
+                           accumulate, ws, stream=None):
+    """modes: list of MODE_*; inputs / grads: lists of dicts by the field names of mecefo_block_inputs_t /
+    mecefo_block_grads_t (a neighbor-mode layer needs H, g_ffn, Wg, Wu, Wd only); lowrank: layer_lowrank(...)
+    or None; policy: RefreshPolicy or None; counters: ctypes int64 array (updated in place) or None."""
+    n = len(modes)
+    p, nbytes = _ws(ws)
+    m = (C.c_int * n)(*[int(x) for x in modes])
+    tin = (BlockInputs * n)(*[_table(BlockInputs, _BLOCK_IN, d) for d in inputs])
+    tout = (BlockGrads * n)(*[_table(BlockGrads, _BLOCK_OUT, d) for d in grads])
+    _check(lib().mecefo_stack_bwd_mixed(C.byref(desc), C.byref(attn), n, m, tin, tout, lowrank, int(side),
+                                        C.byref(policy) if policy is not None else None, counters, _ptr(dOut_top),
+                                        _ptr(dX_bottom), int(accumulate), p, nbytes, _stream(stream)))
 
 
 def mecefo_grad_average(grad_dtype, grads, contributes, out, n_elems, stream=None):

@@ -1227,4 +1227,93 @@ mecefo_status_t mecefo_stack_bwd_skip(const mecefo_ffn_desc_t* desc, int n_layer
   return MECEFO_OK;
 }
 
+
+// ---- Alg. 1 / Alg. 3 bookkeeping and the stack backward with a mode per layer ----------------
+int mecefo_refresh_due(int64_t t, int64_t tau) { return tau >= 1 && t >= 0 && t % tau == 0; }
+
+void mecefo_counters_reset(int64_t* t, int n_layers) {
+  if (!t) return;
+  for (int l = 0; l < n_layers; ++l) t[l] = 0;
+}
+
+mecefo_status_t mecefo_stack_mixed_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
+                                                   int r_gate, int r_up, int r_down, size_t* out_bytes) {
+  size_t full = 0, skip = 0;
+  TRY(mecefo_block_full_workspace_bytes(desc, attn, &full));
+  TRY(mecefo_workspace_bytes(desc, r_gate, r_up, r_down, &skip));
+  if (!out_bytes) return fail(MECEFO_ERR_INVALID_ARG, "out_bytes is NULL");
+  size_t best = full > skip ? full : skip;
+  // projection refresh of the three FFN matrices, one after the other in the same workspace (either side)
+  const int rr[3] = {r_gate, r_up, r_down};
+  for (int i = 0; i < 3; ++i) {
+    if (rr[i] <= 0) continue;
+    const int m = i < 2 ? desc->d_ff : desc->d_model, n = i < 2 ? desc->d_model : desc->d_ff;
+    for (int left = 0; left < 2; ++left) {
+      size_t pw = 0;
+      TRY(mecefo_projection_workspace_bytes(desc->dtype, m, n, rr[i], left, &pw));
+      if (pw > best) best = pw;
+    }
+  }
+  *out_bytes = best;
+  return MECEFO_OK;
+}
+
+mecefo_status_t mecefo_stack_bwd_mixed(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn, int n_layers,
+                                       const mecefo_mode_t* modes, const mecefo_block_inputs_t* in,
+                                       const mecefo_block_grads_t* grads, const mecefo_layer_lowrank_t* lowrank,
+                                       mecefo_side_t side, const mecefo_refresh_policy_t* policy, int64_t* t,
+                                       const void* dOut_top, void* dX_bottom, int accumulate, void* ws,
+                                       size_t ws_bytes, void* hip_stream) {
+  if (n_layers < 1) return fail(MECEFO_ERR_INVALID_ARG, "n_layers must be >= 1");
+  if (!modes || !in || !grads) return fail(MECEFO_ERR_INVALID_ARG, "modes, in and grads are required");
+  if (!desc) return fail(MECEFO_ERR_INVALID_ARG, "descriptor is NULL");
+  bool any_neighbor = false;
+  for (int l = 0; l < n_layers; ++l) {
+    if (modes[l] != MECEFO_MODE_STANDARD && modes[l] != MECEFO_MODE_NEIGHBOR)
+      return fail(MECEFO_ERR_INVALID_ARG, "layer %d: mode must be MECEFO_MODE_STANDARD or MECEFO_MODE_NEIGHBOR", l);
+    any_neighbor |= modes[l] == MECEFO_MODE_NEIGHBOR;
+  }
+  if (any_neighbor && !lowrank) return fail(MECEFO_ERR_INVALID_ARG, "lowrank is required when a layer runs in neighbor mode");
+  if ((policy == nullptr) != (t == nullptr)) return fail(MECEFO_ERR_INVALID_ARG, "policy and t must both be given or both be NULL");
+  if (policy && (policy->tau < 1 || policy->power_iters < 1 || policy->cond_steps < 0 || policy->polish_steps < 0))
+    return fail(MECEFO_ERR_INVALID_ARG, "refresh policy: tau >= 1, power_iters >= 1, cond_steps >= 0, polish_steps >= 0 required");
+  const bool left = side == MECEFO_SIDE_OUTPUT;
+  // the gradient travels down in dX_bottom's buffer: every layer overwrites its dOut with its dX
+  const void* g = dOut_top;
+  for (int l = n_layers - 1; l >= 0; --l) {
+    const mecefo_block_inputs_t& x = in[l];
+    const mecefo_block_grads_t& o = grads[l];
+    mecefo_status_t st;
+    if (modes[l] == MECEFO_MODE_STANDARD) {           // Alg. 3, first branch: exact gradients, MHA included
+      mecefo_block_inputs_t xi = x;
+      xi.dOut = g;
+      mecefo_block_grads_t oi = o;
+      oi.dX = dX_bottom;
+      st = mecefo_block_bwd_full(desc, attn, &xi, &oi, accumulate, ws, ws_bytes, hip_stream);
+    } else {                                          // neighbor branch
+      const mecefo_layer_lowrank_t& q = lowrank[l];
+      if (policy && mecefo_refresh_due(t[l], policy->tau)) {
+        // V1 of the current weights (Alg. 3: every tau neighbor steps of this layer), warm-started from and
+        // written over the layer's present projection
+        const void* W[3] = {x.Wg, x.Wu, x.Wd};
+        const mecefo_proj_t P[3] = {q.Pg, q.Pu, q.Pd};
+        for (int i = 0; i < 3; ++i) {
+          const int m = i < 2 ? desc->d_ff : desc->d_model, n = i < 2 ? desc->d_model : desc->d_ff;
+          const int64_t ldw = i < 2 ? desc->ld_w_fd : desc->ld_w_df;
+          st = mecefo_projection_refresh(desc->dtype, W[i], m, n, ldw, left ? 1 : 0, P[i].P, P[i].ld, P[i].r,
+                                         policy->power_iters, policy->cond_steps, policy->polish_steps,
+                                         const_cast<void*>(P[i].P), P[i].ld, ws, ws_bytes, hip_stream);
+          if (st != MECEFO_OK) return st;
+        }
+      }
+      st = mecefo_block_bwd_skip(desc, x.H, g, x.g_ffn, x.Wg, x.Wu, x.Wd, q.Pg, q.Pu, q.Pd, side, dX_bottom,
+                                 q.dg_ffn, q.dWg, q.dWu, q.dWd, accumulate, ws, ws_bytes, hip_stream);
+      if (st == MECEFO_OK && t) t[l] += 1;            // Alg. 3: the local step counter of this layer
+    }
+    if (st != MECEFO_OK) return st;
+    g = dX_bottom;
+  }
+  return MECEFO_OK;
+}
+
 }  // extern "C"

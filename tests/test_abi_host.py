@@ -122,6 +122,45 @@ def test_localised_gate_sees_one_wrong_column_of_a_large_matrix():
     assert local_relerr(lost, v)["block"] > 0.5
 
 
+def test_refresh_schedule_of_alg3_and_counter_reset_of_alg1():
+    """Alg. 3: the projection of a layer is recomputed when its local step counter is a multiple of tau
+    (steps 0, tau, 2 tau, ... of the node's time as a neighbor); Alg. 1: a failure sets the counters of
+    the layers taken over to zero, so the next neighbor step refreshes again."""
+    tau = 100                                   # the paper's setting (App. E)
+    t = (C.c_int64 * 3)(0, 0, 0)
+    refreshed = []
+    for step in range(250):
+        if step == 130:                         # a second failure: layers taken over anew
+            B.mecefo_counters_reset(t)
+        if B.mecefo_refresh_due(t[0], tau):
+            refreshed.append(step)
+        for l in range(3):
+            t[l] += 1                           # what mecefo_stack_bwd_mixed does per neighbor-mode backward
+    assert refreshed == [0, 100, 130, 230]
+    assert [B.mecefo_refresh_due(x, 1) for x in (0, 1, 2)] == [True, True, True]
+    assert not B.mecefo_refresh_due(5, 0) and not B.mecefo_refresh_due(-1, 100)
+    # argument checks of the driver that consumes the schedule (before anything is enqueued)
+    lib = B.lib()
+    d = B.make_desc(32, 64, 104, B.BF16)
+    a = B.make_attn_desc(2, 16, 4, 64)
+    fake = C.c_void_p(0x10000)
+    modes = (C.c_int * 2)(B.MODE_NEIGHBOR, 7)
+    tin, tout = (B.BlockInputs * 2)(), (B.BlockGrads * 2)()
+    low = (B.LayerLowrank * 2)()
+    st = lib.mecefo_stack_bwd_mixed(C.byref(d), C.byref(a), 2, modes, tin, tout, low, 0, None, None, fake, fake, 0, fake, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "mode" in B.mecefo_last_error()
+    modes[1] = B.MODE_STANDARD
+    st = lib.mecefo_stack_bwd_mixed(C.byref(d), C.byref(a), 2, modes, tin, tout, None, 0, None, None, fake, fake, 0, fake, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "lowrank" in B.mecefo_last_error()
+    pol = B.RefreshPolicy(100, 2, 8, 3)
+    st = lib.mecefo_stack_bwd_mixed(C.byref(d), C.byref(a), 2, modes, tin, tout, low, 0, C.byref(pol), None, fake, fake, 0, fake, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "both" in B.mecefo_last_error()
+    bad = B.RefreshPolicy(0, 2, 8, 3)
+    st = lib.mecefo_stack_bwd_mixed(C.byref(d), C.byref(a), 2, modes, tin, tout, low, 0, C.byref(bad), t, fake, fake, 0, fake, 1 << 30, None)
+    assert st == B.ERR_INVALID_ARG and "tau" in B.mecefo_last_error()
+    assert B.mecefo_stack_mixed_workspace_bytes(d, a, 8, 8, 8) >= B.mecefo_workspace_bytes(d, 8, 8, 8)
+
+
 def test_set_option_validates_names_and_values():
     B.mecefo_set_option("tile", "L8")
     B.mecefo_set_option("tile", "auto")

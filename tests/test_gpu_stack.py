@@ -222,6 +222,127 @@ def test_stack_calls_equal_the_per_layer_calls_bit_for_bit():
             assert np.array_equal(a["grads"][l][k], b["grads"][l][k]), (l, k)
 
 
+def _mixed_setup(seed, modes):
+    """A small bf16 stack whose layers are forwarded one by one in standard mode (everything a
+    standard-mode backward needs is kept), plus gradient buffers filled with NaN canaries."""
+    import ctypes as C
+    n_layers = len(modes)
+    st = Stack(n_layers, 2, 96, 128, 344, 4, 32, "bf16", seed)
+    t = tdtype("bf16")
+    act = lambda: torch.full((st.b, st.d), float("nan"), dtype=t, device="cuda")
+    fws = torch.empty(B.mecefo_block_fwd_workspace_bytes(st.desc, st.attn), dtype=torch.uint8, device="cuda")
+    saved, x = [], st.X0d
+    for l in range(n_layers):
+        e = st.dev_layers[l]
+        out = dict(Out=act(), H=act(), Q=act(), K=act(), V=act(), O=act(),
+                   L=torch.full((st.batch * st.heads * st.seq,), float("nan"), device="cuda"))
+        B.mecefo_block_fwd(st.desc, st.attn, dict(X=x, **e), out, fws)
+        saved.append(dict(X=x, **{k: out[k] for k in ("H", "Q", "K", "V", "O", "L")}))
+        x = out["Out"]
+    torch.cuda.synchronize()
+    nanf = lambda *shape: torch.full(shape, float("nan"), device="cuda")
+    d, f = st.d, st.f
+    grads = [dict(dg_attn=nanf(d), dg_ffn=nanf(d), dWq=nanf(d, d), dWk=nanf(d, d), dWv=nanf(d, d), dWo=nanf(d, d),
+                  dWg=nanf(f, d), dWu=nanf(f, d), dWd=nanf(d, st.ldf)) for _ in range(n_layers)]
+    inputs = [dict(dOut=st.dOd, **saved[l], **st.dev_layers[l]) for l in range(n_layers)]
+    low = B.layer_lowrank([dict(Pg=B.proj(P[0], st.r), Pu=B.proj(P[1], st.r), Pd=B.proj(P[2], st.r),
+                                dg_ffn=g["dg_ffn"], dWg=g["dWg"], dWu=g["dWu"], dWd=g["dWd"])
+                           for P, g in zip(st.Pdev, grads)])
+    ws = torch.empty(B.mecefo_stack_mixed_workspace_bytes(st.desc, st.attn, st.r, st.r, st.r), dtype=torch.uint8, device="cuda")
+    return st, inputs, grads, low, ws, C
+
+
+def test_mixed_stack_standard_and_neighbor_layers():
+    """The skip on a subset of the layers (Sec. 5, extension paragraph): layers 1 and 3 run in neighbor
+    mode, layers 0 and 2 in standard mode.  The driver must equal the chain of per-layer calls bit for bit
+    (those are gated against the oracle layer by layer elsewhere), a neighbor-mode layer must leave its
+    MHA gradient buffers untouched, and the top layer (whose upstream gradient is an input) is compared
+    with the oracle at the stated tolerance."""
+    modes = [B.MODE_STANDARD, B.MODE_NEIGHBOR, B.MODE_STANDARD, B.MODE_NEIGHBOR]
+    st, inputs, grads, low, ws, _ = _mixed_setup(11, modes)
+    dX = torch.full((st.b, st.d), float("nan"), dtype=tdtype("bf16"), device="cuda")
+    B.mecefo_stack_bwd_mixed(st.desc, st.attn, modes, inputs, [dict(dX=dX, **g) for g in grads], low, B.SIDE_INPUT,
+                             None, None, st.dOd, dX, 0, ws)
+    torch.cuda.synchronize()
+    got = [{k: host(v) for k, v in g.items()} for g in grads]
+    got_dX = host(dX)
+    for l, m in enumerate(modes):
+        for k in ("dg_attn", "dWq", "dWk", "dWv", "dWo"):
+            if m == B.MODE_NEIGHBOR:
+                assert np.all(np.isnan(got[l][k])), (l, k)          # Sec. 3.2: no MHA gradient from a neighbor-mode layer
+            else:
+                assert np.all(np.isfinite(got[l][k])), (l, k)
+        for k in ("dg_ffn", "dWg", "dWu"):
+            assert np.all(np.isfinite(got[l][k])), (l, k)
+    # the same chain through the per-layer entry points
+    g = st.dOd.clone()
+    ref = [dict((k, torch.full_like(v, float("nan"))) for k, v in gr.items()) for gr in grads]
+    for l in range(len(modes) - 1, -1, -1):
+        e, P = st.dev_layers[l], st.Pdev[l]
+        if modes[l] == B.MODE_NEIGHBOR:
+            B.mecefo_block_bwd_skip(st.desc, inputs[l]["H"], g, e["g_ffn"], e["Wg"], e["Wu"], e["Wd"], B.proj(P[0], st.r),
+                                    B.proj(P[1], st.r), B.proj(P[2], st.r), B.SIDE_INPUT, g, ref[l]["dg_ffn"],
+                                    ref[l]["dWg"], ref[l]["dWu"], ref[l]["dWd"], 0, ws)
+        else:
+            B.mecefo_block_bwd_full(st.desc, st.attn, dict(inputs[l], dOut=g), dict(dX=g, **ref[l]), 0, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(g), got_dX)
+    for l in range(len(modes)):
+        for k, v in ref[l].items():
+            assert np.array_equal(host(v), got[l][k], equal_nan=True), (l, k)
+    top = len(modes) - 1
+    p = st.params[top]
+    want = O.block_bwd_skip(host(inputs[top]["H"]), st.dOut, p["g_ffn"], p["Wg"], p["Wu"], p["Wd"], *p["P"], EPS)
+    for k, kk in (("dg_ffn", "dgamma"), ("dWg", "dWg"), ("dWu", "dWu")):
+        assert relerr(got[top][k], want[kk]) <= TOL["bf16"], (k, relerr(got[top][k], want[kk]))
+    assert relerr(got[top]["dWd"][:, :st.f], want["dWd"]) <= TOL["bf16"]
+
+
+def test_mixed_stack_refreshes_projections_when_the_counter_is_due():
+    """Alg. 3's refresh branch wired into the driver: with tau = 10 and counters (0, 0, 0, 5) the neighbor-mode
+    layer 1 (t = 0) recomputes its three projections before its backward, layer 3 (t = 5) reuses them; the
+    standard-mode layers keep their counters; every neighbor-mode layer's counter grows by one."""
+    modes = [B.MODE_STANDARD, B.MODE_NEIGHBOR, B.MODE_STANDARD, B.MODE_NEIGHBOR]
+    st, inputs, grads, low, ws, C = _mixed_setup(12, modes)
+    before = [[host(P) for P in layer] for layer in st.Pdev]
+    # what the refresh of layer 1 must produce: the refresh call itself with the same arguments
+    pol = B.RefreshPolicy(10, 2, 8, 3)
+    e = st.dev_layers[1]
+    expect = []
+    for W, m, n, ldw, P in ((e["Wg"], st.f, st.d, st.d, st.Pdev[1][0]), (e["Wu"], st.f, st.d, st.d, st.Pdev[1][1]),
+                            (e["Wd"], st.d, st.f, st.ldf, st.Pdev[1][2])):
+        out = torch.empty_like(P)
+        pws = torch.empty(B.mecefo_projection_workspace_bytes(B.BF16, m, n, st.r, 0), dtype=torch.uint8, device="cuda")
+        B.mecefo_projection_refresh(B.BF16, W, m, n, ldw, 0, P, P.stride(0), st.r, 2, 8, 3, out, out.stride(0), pws)
+        expect.append(host(out))
+    t = (C.c_int64 * 4)(0, 0, 0, 5)
+    dX = torch.full((st.b, st.d), float("nan"), dtype=tdtype("bf16"), device="cuda")
+    B.mecefo_stack_bwd_mixed(st.desc, st.attn, modes, inputs, [dict(dX=dX, **g) for g in grads], low, B.SIDE_INPUT,
+                             pol, t, st.dOd, dX, 0, ws)
+    torch.cuda.synchronize()
+    assert list(t) == [0, 1, 0, 6]
+    after = [[host(P) for P in layer] for layer in st.Pdev]
+    for i in range(3):
+        assert np.array_equal(after[3][i], before[3][i])              # not due: reused
+        assert np.array_equal(after[0][i], before[0][i]) and np.array_equal(after[2][i], before[2][i])
+        assert not np.array_equal(after[1][i], before[1][i])          # due: recomputed in place ...
+        assert np.array_equal(after[1][i], expect[i])                 # ... by the refresh call, bit for bit
+        Pn = after[1][i][:, :st.r].astype(np.float64)
+        assert np.linalg.norm(Pn.T @ Pn - np.eye(st.r), 2) < 1e-2     # orthonormal basis (bf16 floor)
+    # the gradients of layer 1 were formed with the refreshed projection
+    p = st.params[1]
+    H1 = host(inputs[1]["H"])
+    assert np.all(np.isfinite(host(grads[1]["dWg"])))
+    # second step: nothing is due any more, counters keep counting
+    B.mecefo_stack_bwd_mixed(st.desc, st.attn, modes, inputs, [dict(dX=dX, **g) for g in grads], low, B.SIDE_INPUT,
+                             pol, t, st.dOd, dX, 0, ws)
+    torch.cuda.synchronize()
+    assert list(t) == [0, 2, 0, 7]
+    assert all(np.array_equal(host(P), after[1][i]) for i, P in enumerate(st.Pdev[1]))
+    B.mecefo_counters_reset(t)                                          # Alg. 1: a new failure
+    assert list(t) == [0, 0, 0, 0]
+
+
 def test_whole_stack_pass_in_one_hip_graph():
     """Forward + chained backward of the stack captured once and replayed with fresh inputs, with
     eager work and synchronisations between the replays; every replay must equal the eager pass."""
