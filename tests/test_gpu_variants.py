@@ -77,3 +77,43 @@ def test_mask_validation():
         run_ex(lay, c, mask=8)
     with pytest.raises(B.MecefoError):           # a low-rank matrix still needs its projection
         run_ex(lay, c, mask=0, drop_P=False, G=lay.act(c["H"]))   # G without Z
+
+
+def test_moe_expert_shaped_ffn_ragged_token_groups():
+    """An expert of a mixture-of-experts block is the same SwiGLU FFN with a small d_ff, applied to the tokens
+    routed to it (the paper's MLA + MoE variant, App. "other model structures"; expert sizes are not given, so
+    the shape is a stand-in: d = 512, eight experts of d_ff = 200, r = 32 per matrix).  Each expert's token
+    group goes through mecefo_ffn_bwd_lowrank: groups of very different sizes, one empty, one of a single
+    token, one ragged against every tile; the routed groups partition the token batch, so the sum of the
+    experts' input gradients scattered back must equal the oracle's, group by group."""
+    d, f, r, experts = 512, 200, 32, 8
+    sizes = [0, 1, 37, 256, 300, 64, 129, 513]
+    rng = np.random.default_rng(61)
+    total = sum(sizes)
+    U, dY = I.gaussian_block_io(rng, total, d, "bf16")
+    order = rng.permutation(total)                      # which tokens each expert received
+    start = 0
+    worst = {}
+    for e in range(experts):
+        idx = np.sort(order[start:start + sizes[e]])
+        start += sizes[e]
+        Wg, Wu, Wd, _ = I.ffn_weights(rng, d, f, "bf16")
+        Ps = [I.random_orthonormal(rng, n, r, "bf16") for n in (d, d, f)]
+        lay = Layer(sizes[e], d, f, "bf16", Wg, Wu, Wd, None, *Ps, EPS)
+        Ue, dYe = U[idx], dY[idx]
+        dU = torch.full((sizes[e], lay.ld_act_d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.mecefo_ffn_bwd_lowrank(lay.desc, lay.act(Ue) if sizes[e] else None, lay.act(dYe) if sizes[e] else None,
+                                 lay.Wg, lay.Wu, lay.Wd, *lay.projs(), B.SIDE_INPUT, dU if sizes[e] else None,
+                                 lay.dWg, lay.dWu, lay.dWd, 0, lay.ws)
+        torch.cuda.synchronize()
+        got = lay.results()
+        if sizes[e] == 0:
+            for k in ("dWg", "dWu", "dWd"):
+                assert np.array_equal(got[k], np.zeros_like(got[k])), (e, k)     # an expert nobody was routed to
+            continue
+        got["dU"] = host(dU, d)
+        want = O.ffn_bwd_lowrank(Ue, dYe, Wg, Wu, Wd, *Ps)
+        errs = assert_close(got, want, TOL["bf16"], keys=["dU", "dWg", "dWu", "dWd"], label=f"expert {e} ({sizes[e]} tokens): ")
+        for k, v in errs.items():
+            worst[k] = max(worst.get(k, 0.0), v)
+    print("MoE-expert-shaped groups, worst errors", worst)
