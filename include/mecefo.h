@@ -128,6 +128,23 @@ mecefo_status_t mecefo_block_bwd_skip(const mecefo_ffn_desc_t* desc, const void*
     void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
     void* ws, size_t ws_bytes, void* hip_stream);
 
+/* mecefo_block_bwd_skip for callers that can neither allocate nor bring a workspace: code under HIP graph
+ * capture, tight serving or training loops and harnesses that forbid hipMalloc.  Same arguments and results
+ * as mecefo_block_bwd_skip without ws / ws_bytes: the scratch is a buffer of MECEFO_NOALLOC_SCRATCH_BYTES
+ * that the library holds in static device memory on every GPU it is loaded on (until the process ends), so
+ * the call itself allocates and frees nothing.  Shapes whose workspace (mecefo_workspace_bytes) exceeds that
+ * size are rejected with MECEFO_ERR_WORKSPACE_TOO_SMALL before anything is enqueued (64 MiB covers e.g.
+ * 2048 tokens at d = 512, f = 1376, r = 128; the 7B-shaped layer needs 0.75 GiB and the caller's own
+ * workspace).  All calls on one GPU share that GPU's buffer and it keeps the last call's contents: calls
+ * that overlap in time on one GPU (different streams or host threads) race; order them on one stream. */
+#define MECEFO_NOALLOC_SCRATCH_BYTES (64u << 20)
+mecefo_status_t mecefo_block_bwd_skip_noalloc(const mecefo_ffn_desc_t* desc, const void* H,
+    const void* dOut, const void* gamma,
+    const void* Wg, const void* Wu, const void* Wd,
+    mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+    void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
+    void* hip_stream);
+
 /* ---- Standard-mode backward of one block (Alg. 3, first branch: the rank runs its own layer
  * without approximation).  Block: H = X + MHA(norm(X; g_attn)); Out = H + FFN(norm(H; g_ffn));
  * MHA = causal multi-head attention with rotary position embedding (pairs (j, j + dh/2) of a

@@ -108,6 +108,8 @@ def lib() -> C.CDLL:
                                          [C.c_int, _vp, C.c_size_t, _vp])
     L.mecefo_block_bwd_skip.argtypes = ([D] + [_vp] * 6 + [Proj] * 3 + [C.c_int] + [_vp] * 5 +
                                         [C.c_int, _vp, C.c_size_t, _vp])
+    L.mecefo_block_bwd_skip_noalloc.argtypes = ([D] + [_vp] * 6 + [Proj] * 3 + [C.c_int] + [_vp] * 5 + [C.c_int, _vp])
+    L.mecefo_block_bwd_skip_noalloc.restype = C.c_int
     L.mecefo_block_bwd_skip_ex.argtypes = ([D] + [_vp] * 6 + [Proj] * 3 + [C.c_int, C.POINTER(SkipOptions)] + [_vp] * 5 +
                                            [C.c_int, _vp, C.c_size_t, _vp])
     L.mecefo_block_full_workspace_bytes.argtypes = [D, C.POINTER(AttnDesc), C.POINTER(C.c_size_t)]
@@ -222,6 +224,16 @@ def mecefo_block_bwd_skip(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX
     _check(lib().mecefo_block_bwd_skip(C.byref(desc), _ptr(H), _ptr(dOut), _ptr(gamma), _ptr(Wg), _ptr(Wu),
                                        _ptr(Wd), Pg, Pu, Pd, int(side), _ptr(dX), _ptr(dgamma), _ptr(dWg),
                                        _ptr(dWu), _ptr(dWd), int(accumulate), p, n, _stream(stream)))
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def mecefo_block_bwd_skip_noalloc(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX, dgamma, dWg, dWu, dWd,
+                                  accumulate, stream=None):
+    _check(lib().mecefo_block_bwd_skip_noalloc(C.byref(desc), _ptr(H), _ptr(dOut), _ptr(gamma), _ptr(Wg), _ptr(Wu),
+                                               _ptr(Wd), Pg, Pu, Pd, int(side), _ptr(dX), _ptr(dgamma), _ptr(dWg),
+                                               _ptr(dWu), _ptr(dWd), int(accumulate), _stream(stream)))
 
 
 def mecefo_block_bwd_skip_ex(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX, dgamma, dWg, dWu, dWd,

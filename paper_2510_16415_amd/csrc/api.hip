@@ -580,6 +580,31 @@ mecefo_status_t check_lowrank_args(const Ctx& c, const mecefo_proj_t P[3], mecef
 
 }  // namespace
 
+// ---- scratch of the entry point that allocates nothing ------------------------------------
+// Device memory that exists once per GPU from the moment the code object is loaded there.  In host code
+// the name below stands for the symbol, not for an address: the address on the current device comes from
+// hipGetSymbolAddress and is kept per device.
+static __device__ __align__(256) unsigned char scratch[MECEFO_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+mecefo_status_t scratch_on_current_device(void** out) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MECEFO_ERR_UNSUPPORTED, "device index %d is beyond the %d the scratch table holds", dev, kMaxDevices);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {   // several threads may resolve at once: every one of them gets the same address
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(MECEFO_ERR_LAUNCH, "hipGetSymbolAddress returned a NULL scratch address");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return MECEFO_OK;
+}
+}  // namespace
+
 extern "C" {
 
 const char* mecefo_last_error(void) { return g_err; }
@@ -591,6 +616,8 @@ mecefo_status_t mecefo_init(void) {
   HIP_TRY(prepare_gemm_bf16_tn());
   HIP_TRY(prepare_attention_fwd());
   HIP_TRY(prepare_attention_bwd());
+  void* p = nullptr;
+  TRY(scratch_on_current_device(&p));
   return MECEFO_OK;
 }
 
@@ -1227,6 +1254,25 @@ mecefo_status_t mecefo_stack_bwd_skip(const mecefo_ffn_desc_t* desc, int n_layer
   return MECEFO_OK;
 }
 
+
+mecefo_status_t mecefo_block_bwd_skip_noalloc(const mecefo_ffn_desc_t* desc, const void* H, const void* dOut,
+                                              const void* gamma, const void* Wg, const void* Wu, const void* Wd,
+                                              mecefo_proj_t Pg, mecefo_proj_t Pu, mecefo_proj_t Pd, mecefo_side_t side,
+                                              void* dX, void* dgamma, void* dWg, void* dWu, void* dWd, int accumulate,
+                                              void* hip_stream) {
+  size_t need = 0;
+  TRY(mecefo_workspace_bytes(desc, Pg.r > 0 ? Pg.r : 0, Pu.r > 0 ? Pu.r : 0, Pd.r > 0 ? Pd.r : 0, &need));
+  if (need > (size_t)MECEFO_NOALLOC_SCRATCH_BYTES)
+    return fail(MECEFO_ERR_WORKSPACE_TOO_SMALL,
+                "this shape needs %zu bytes of scratch; the static buffer of mecefo_block_bwd_skip_noalloc holds %zu "
+                "(use mecefo_block_bwd_skip with a workspace of the caller's)", need, (size_t)MECEFO_NOALLOC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  TRY(scratch_on_current_device(&ws));
+  // Nothing in the scratch has to start at zero: every region of the workspace layout is written by a
+  // kernel of this call before a later kernel of the same call reads it.
+  return mecefo_block_bwd_skip(desc, H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, side, dX, dgamma, dWg, dWu, dWd, accumulate,
+                               ws, (size_t)MECEFO_NOALLOC_SCRATCH_BYTES, hip_stream);
+}
 
 // ---- Alg. 1 / Alg. 3 bookkeeping and the stack backward with a mode per layer ----------------
 int mecefo_refresh_due(int64_t t, int64_t tau) { return tau >= 1 && t >= 0 && t % tau == 0; }
