@@ -247,6 +247,7 @@ def main():
         out["neighbor_stack"] = neighbor_stack(B, torch, I)
         out["step_compositions_per_layer"] = step_compositions(B, torch, I)
         out["per_config_one_layer"] = per_config_lines(B, torch, I)
+        out["vendor_gemm_reference"] = vendor_gemm_reference(torch, b, d, f, args.data)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
@@ -341,6 +342,44 @@ def overhead(B, torch, desc, b, d, f, r, ldf, U, dY, Wg, Wu, Wd, projs, dU, dWg,
         "note": "block_full: FFN recomputed from H with exact weight gradients + attention backward from "
                 "saved Q, K, V, O, L (fabricated outside the timed region); all kernels are this library's",
     }
+
+
+def vendor_gemm_reference(torch, b, d, f, data):
+    """Context, not a target and not on the product path: the vendor GEMM library (torch.matmul on bf16
+    tensors) on the three large products of the step, same shapes, same kind of operands, same box and
+    minute.  The matrix cores are power-limited on Gaussian operands (the shader clock drops well below
+    2.4 GHz), so what any kernel can reach on this workload is best read next to this line."""
+    dev, bf = torch.device("cuda:0"), torch.bfloat16
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+
+    def mk(rows, cols, std):
+        if data == "zeros":
+            return torch.zeros(rows, cols, dtype=bf, device=dev)
+        return (torch.randn(rows, cols, generator=g, device=dev) * std).to(bf)
+
+    U, dOut, dGZ = mk(b, d, 1.0), mk(b, d, 1.0), mk(b, 2 * f, 1.0)
+    Wgu, Wd = mk(2 * f, d, 0.02), mk(d, f, 0.02)
+    cases = {
+        "recompute_shape_b_x_2f_x_d_NT": (lambda: torch.matmul(U, Wgu.t()), 4 * b * d * f),
+        "dgrad_down_shape_b_x_f_x_d_NN": (lambda: torch.matmul(dOut, Wd), 2 * b * d * f),
+        "dgrad_gate_up_shape_b_x_d_x_2f_NN": (lambda: torch.matmul(dGZ, Wgu), 4 * b * d * f),
+    }
+    out = {}
+    for name, (fn, fl) in cases.items():
+        for _ in range(5):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(fl / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12, 1)
+    out["unit"] = "TFLOP/s"
+    out["note"] = ("torch.matmul (vendor library) on plain products of the same shapes; no fused SwiGLU "
+                   "backward, no second K segment: a context figure for the power-limited ceiling")
+    return out
 
 
 def projection_refresh(B, torch, Wg, Wd, Pg, Pd, d, f, ldf, r, deg_block_ms, tau=100):
