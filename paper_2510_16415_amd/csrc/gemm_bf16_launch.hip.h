@@ -52,10 +52,13 @@ inline int bf16_tile_choice(const GemmLaunch& g) {
   return c;
 }
 
-// Two 64 KiB stages, refilled one stage ahead.  (Measured alternatives that lost: four 32-K stages
-// -- the 64-byte row pieces double the L2 request count; three A + two B buffers, or a second
-// barrier that lets two fills overlap; touching the cache lines of later stages to pull them into
-// L2 early cost 8 % -- the kernel is bound by L2 request throughput, not by fill latency.)
+// Two 64 KiB stages, refilled one stage ahead.  Measured alternatives that lost: four 32-K stages
+// (64-byte row pieces double the L2 request count); rings of three buffers, symmetric or A2+B3 /
+// A3+B2; a second barrier that lets two fills overlap; one operand staged through registers two
+// stages ahead; line-touch prefetch of later stages (+8 %).  Fill latency is not what bounds the
+// loop (a fills-only loop runs a stage in 0.9-1.3 us, the full loop gives it 1.4): LDS traffic of
+// fills plus fragment reads and MFMA issue are both near a stage's length, and on Gaussian operands
+// the matrix cores are power-limited.
 using PipeA = DtlPipe<64, 2>;
 
 struct NoPipe { static constexpr int LDS_BYTES = 0; };
