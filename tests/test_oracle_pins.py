@@ -377,6 +377,41 @@ def test_stack_forward_shapes_and_consistency():
     assert relerr(Hs[-1] + Y, X_last) < 1e-12
 
 
+def test_stack_forward_and_loss_gradient_match_a_torch_module_chain():
+    """The harness that manufactures H_l and dOut for the stack configs (embedding lookup, L blocks,
+    final norm, LM head, summed next-token cross-entropy) against the same model written with torch ops
+    and differentiated by autograd: every stored H_l, the last block's output, the loss and its gradient
+    with respect to the last block's output."""
+    from paper_2510_16415_amd import inputs
+    cfg = inputs.Config("T", 9, 16, 24, 2, 3, 5, 4, 2, "f32", stack=True)
+    params = inputs.stack_params(cfg)
+    V = 37
+    params["emb"], params["lm_head"] = params["emb"][:V], params["lm_head"][:V]
+    batch, seq = 2, 5
+    ids = np.random.default_rng(3).integers(0, V, size=(batch, seq))
+    Hs, X_last = O.stack_forward(ids, params, cfg.heads, EPS)
+    loss, dX_last = O.next_token_loss_grad(X_last, params, ids, EPS)
+
+    X = torch.tensor(np.asarray(params["emb"], dtype=np.float64))[torch.tensor(ids.reshape(-1))]
+    t_H = []
+    for p_l in params["blocks"]:
+        blk = _TorchBlock({k: np.asarray(v, dtype=np.float64) for k, v in p_l.items()}, cfg.heads, batch, seq)
+        X, H = blk(X)
+        t_H.append(H.detach().numpy())
+    Xl = X.detach().clone().requires_grad_(True)
+    xn = _TorchBlock.norm(Xl, torch.tensor(np.asarray(params["g_final"], dtype=np.float64)))
+    logits = (xn @ torch.tensor(np.asarray(params["lm_head"], dtype=np.float64)).T).view(batch, seq, V)
+    tgt = torch.tensor(ids)[:, 1:].reshape(-1)
+    t_loss = torch.nn.functional.cross_entropy(logits[:, :-1].reshape(-1, V), tgt, reduction="sum")
+    t_loss.backward()
+    assert len(Hs) == len(t_H) == cfg.layers
+    for l, (a, b_) in enumerate(zip(Hs, t_H)):
+        assert relerr(a, b_) < 1e-12, l
+    assert relerr(X_last, X.detach().numpy()) < 1e-12
+    assert abs(loss - t_loss.item()) < 1e-10 * abs(t_loss.item())
+    assert relerr(dX_last, Xl.grad.numpy()) < 1e-10
+
+
 def test_saved_logsumexp_matches_library_routine_and_softmax():
     """The log-sum-exp that the forward keeps for the backward: checked against scipy's routine on
     the scaled, causally masked scores rebuilt from the cached Q and K, and exp(score - L) must
