@@ -183,8 +183,12 @@ def make_desc(tokens, d_model, d_ff, dtype, grad_dtype=F32, ld_act_d=None, ld_ac
 
 
 def proj(P, r=None, ld=None) -> Proj:
-    """Projection argument from a 2-D row-major tensor [dim x >=r]."""
-    return Proj(P.data_ptr(), int(r if r is not None else P.shape[1]), int(ld if ld is not None else P.stride(0)))
+    """Projection argument from a 2-D row-major tensor [dim x >=r].  The struct holds a raw device pointer;
+    it also keeps a reference to the tensor, so that the memory cannot go back to the allocator while the
+    argument is alive."""
+    pr = Proj(P.data_ptr(), int(r if r is not None else P.shape[1]), int(ld if ld is not None else P.stride(0)))
+    pr._tensor = P
+    return pr
 
 
 def mecefo_workspace_bytes(desc: FfnDesc, r_gate=0, r_up=0, r_down=0) -> int:

@@ -34,6 +34,13 @@ def dev(x: np.ndarray, dtype: str, ld: int | None = None, fill: float = float("n
     return t.to(tdtype(dtype)).cuda()
 
 
+def poisoned_ws(nbytes: int) -> torch.Tensor:
+    """Workspace for a library call with every byte 0xFF (NaN as bf16 and as fp32, -1 as an integer): a
+    kernel that reads workspace bytes no earlier kernel of the same call has written shows up as a
+    non-finite output instead of depending on what the allocator handed out."""
+    return torch.full((max(int(nbytes), 1),), 255, dtype=torch.uint8, device="cuda")
+
+
 def host(t: torch.Tensor, cols: int | None = None) -> np.ndarray:
     a = t.detach().float().cpu().numpy()
     return a if cols is None else a[:, :cols]
@@ -66,7 +73,7 @@ class Layer:
                                 B.F32 if grad_dtype == "f32" else (B.BF16 if dtype == "bf16" else B.F32),
                                 self.ld_act_d, self.ld_act_f, self.ld_w_fd, self.ld_w_df, eps)
         nbytes = B.mecefo_workspace_bytes(self.desc, *self.r)
-        self.ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.ws = poisoned_ws(nbytes)
         gt = torch.float32 if grad_dtype == "f32" else tdtype(dtype)
         self.dWg = torch.full((f, self.ld_w_fd), float("nan"), dtype=gt, device="cuda")
         self.dWu = torch.full((f, self.ld_w_fd), float("nan"), dtype=gt, device="cuda")

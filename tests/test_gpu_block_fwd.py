@@ -8,7 +8,7 @@ import torch
 from oracle import mecefo_oracle as O
 from paper_2510_16415_amd import binding as B
 from paper_2510_16415_amd import inputs as I
-from gpu_util import TOL, assert_close, dev, host, relerr, tdtype
+from gpu_util import TOL, assert_close, dev, host, relerr, tdtype, poisoned_ws
 from test_gpu_full_block import FullBlock, GRADS, make_case, token_major
 
 pytestmark = pytest.mark.gpu
@@ -24,7 +24,7 @@ class Forward:
         self.out = {k: torch.full((b, ld), nan, dtype=t, device="cuda") for k in ("Out", "H", "Q", "K", "V", "O")}
         self.out["L"] = torch.full((batch * heads * seq,), nan, dtype=torch.float32, device="cuda")
         self.inp = {k: blk.inp[k] for k in ("X", "g_attn", "g_ffn", "Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd")}
-        self.ws = torch.empty(B.mecefo_block_fwd_workspace_bytes(blk.desc, blk.attn), dtype=torch.uint8, device="cuda")
+        self.ws = poisoned_ws(B.mecefo_block_fwd_workspace_bytes(blk.desc, blk.attn))
 
     def run(self, neighbor=False):
         out = {k: v for k, v in self.out.items() if not neighbor or k in ("Out", "H")}

@@ -12,7 +12,7 @@ import torch
 from oracle import mecefo_oracle as O
 from paper_2510_16415_amd import binding as B
 from paper_2510_16415_amd import inputs as I
-from gpu_util import TOL, assert_close, dev, host, tdtype
+from gpu_util import TOL, assert_close, dev, host, tdtype, poisoned_ws
 
 pytestmark = pytest.mark.gpu
 EPS = 1e-6
@@ -76,7 +76,7 @@ class FullBlock:
             self.out[k] = torch.full((d, self.ld_d), nan, dtype=gt, device="cuda")
         for k in ("dWg", "dWu"):
             self.out[k] = torch.full((f, self.ld_d), nan, dtype=gt, device="cuda")
-        self.ws = torch.empty(B.mecefo_block_full_workspace_bytes(self.desc, self.attn), dtype=torch.uint8, device="cuda")
+        self.ws = poisoned_ws(B.mecefo_block_full_workspace_bytes(self.desc, self.attn))
 
     def run(self, accumulate=0, alias=False):
         out = dict(self.out)

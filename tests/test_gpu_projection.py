@@ -16,7 +16,7 @@ import torch
 from oracle import mecefo_oracle as O
 from paper_2510_16415_amd import binding as B
 from paper_2510_16415_amd import inputs as I
-from gpu_util import dev, host, tdtype, up8
+from gpu_util import dev, host, tdtype, up8, poisoned_ws
 
 pytestmark = pytest.mark.gpu
 
@@ -36,7 +36,7 @@ def refresh(W, V0, r, dtype, left=0, iters=8, cond=8, polish=5, pad=0):
     Wd, Vd = dev(W, dtype, ldw), dev(V0, dtype, ldv)
     Pd = torch.full((dim, ldv), float("nan"), dtype=tdtype(dtype), device="cuda")
     dt = B.BF16 if dtype == "bf16" else B.F32
-    ws = torch.empty(B.mecefo_projection_workspace_bytes(dt, m, n, r, left), dtype=torch.uint8, device="cuda")
+    ws = poisoned_ws(B.mecefo_projection_workspace_bytes(dt, m, n, r, left))
     B.mecefo_projection_refresh(dt, Wd, m, n, ldw, left, Vd, ldv, r, iters, cond, polish, Pd, ldv, ws)
     torch.cuda.synchronize()
     P = host(Pd, r)

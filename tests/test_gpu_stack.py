@@ -8,7 +8,7 @@ import torch
 from oracle import mecefo_oracle as O
 from paper_2510_16415_amd import binding as B
 from paper_2510_16415_amd import inputs as I
-from gpu_util import TOL, dev, host, relerr, tdtype, up8
+from gpu_util import TOL, dev, host, relerr, tdtype, up8, poisoned_ws
 
 pytestmark = pytest.mark.gpu
 EPS = 1e-6
@@ -130,7 +130,7 @@ class Stack:
                            dWd=torch.full((d, self.ldf), float("nan"), device="cuda")) for _ in range(n_layers)]
         self.lr = B.layer_lowrank([dict(Pg=B.proj(P[0], r), Pu=B.proj(P[1], r), Pd=B.proj(P[2], r), **g)
                                    for P, g in zip(self.Pdev, self.grads)])
-        self.ws = torch.empty(B.mecefo_stack_workspace_bytes(self.desc, self.attn, r, r, r), dtype=torch.uint8, device="cuda")
+        self.ws = poisoned_ws(B.mecefo_stack_workspace_bytes(self.desc, self.attn, r, r, r))
 
     def forward(self):
         B.mecefo_stack_fwd_neighbor(self.desc, self.attn, self.lw, self.X0d, self.H, self.Xout, self.ws)
@@ -205,7 +205,7 @@ def test_stack_calls_equal_the_per_layer_calls_bit_for_bit():
     st.backward()
     a = st.results()
     # the same chain through the single-block entry points
-    bws = torch.empty(B.mecefo_workspace_bytes(st.desc, st.r, st.r, st.r), dtype=torch.uint8, device="cuda")
+    bws = poisoned_ws(B.mecefo_workspace_bytes(st.desc, st.r, st.r, st.r))
     g = st.dOd.clone()
     for l in range(2, -1, -1):
         e, P, G = st.dev_layers[l], st.Pdev[l], st.grads[l]
@@ -230,7 +230,7 @@ def _mixed_setup(seed, modes):
     st = Stack(n_layers, 2, 96, 128, 344, 4, 32, "bf16", seed)
     t = tdtype("bf16")
     act = lambda: torch.full((st.b, st.d), float("nan"), dtype=t, device="cuda")
-    fws = torch.empty(B.mecefo_block_fwd_workspace_bytes(st.desc, st.attn), dtype=torch.uint8, device="cuda")
+    fws = poisoned_ws(B.mecefo_block_fwd_workspace_bytes(st.desc, st.attn))
     saved, x = [], st.X0d
     for l in range(n_layers):
         e = st.dev_layers[l]
@@ -248,7 +248,7 @@ def _mixed_setup(seed, modes):
     low = B.layer_lowrank([dict(Pg=B.proj(P[0], st.r), Pu=B.proj(P[1], st.r), Pd=B.proj(P[2], st.r),
                                 dg_ffn=g["dg_ffn"], dWg=g["dWg"], dWu=g["dWu"], dWd=g["dWd"])
                            for P, g in zip(st.Pdev, grads)])
-    ws = torch.empty(B.mecefo_stack_mixed_workspace_bytes(st.desc, st.attn, st.r, st.r, st.r), dtype=torch.uint8, device="cuda")
+    ws = poisoned_ws(B.mecefo_stack_mixed_workspace_bytes(st.desc, st.attn, st.r, st.r, st.r))
     return st, inputs, grads, low, ws, C
 
 
@@ -312,7 +312,7 @@ def test_mixed_stack_refreshes_projections_when_the_counter_is_due():
     for W, m, n, ldw, P in ((e["Wg"], st.f, st.d, st.d, st.Pdev[1][0]), (e["Wu"], st.f, st.d, st.d, st.Pdev[1][1]),
                             (e["Wd"], st.d, st.f, st.ldf, st.Pdev[1][2])):
         out = torch.empty_like(P)
-        pws = torch.empty(B.mecefo_projection_workspace_bytes(B.BF16, m, n, st.r, 0), dtype=torch.uint8, device="cuda")
+        pws = poisoned_ws(B.mecefo_projection_workspace_bytes(B.BF16, m, n, st.r, 0))
         B.mecefo_projection_refresh(B.BF16, W, m, n, ldw, 0, P, P.stride(0), st.r, 2, 8, 3, out, out.stride(0), pws)
         expect.append(host(out))
     t = (C.c_int64 * 4)(0, 0, 0, 5)
