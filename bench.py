@@ -647,6 +647,21 @@ def cpu_baseline(cfg):
         legs["fp32_one_thread"] = {"value": round(p1 * sample / dt1, 1), "unit": "tokens/s", "cores": 1,
                                    "sample": f"{p1} pass(es) over the first {sample} tokens (the token-independent "
                                              f"expand products of Eq. (2) included once per pass), float32 numpy, {dt1:.1f} s"}
+    # Pure-loop form (explicit index sums, no numpy) on the tiny config C1's layer shape, a few tokens.
+    from oracle import mecefo_loops as LO
+    c1 = I.CONFIGS["C1"]
+    rng1 = I.rng_for(c1.index, 7)
+    W1 = I.ffn_weights(rng1, c1.d_model, c1.d_ff, c1.dtype)
+    tok = 4
+    H1, dO1 = I.gaussian_block_io(rng1, tok, c1.d_model, c1.dtype)
+    P1 = [I._normal(rng1, (n, c1.rank), n ** -0.5) for n in (c1.d_model, c1.d_model, c1.d_ff)]
+    args = [x.tolist() for x in (H1, dO1, W1[3], W1[0], W1[1], W1[2], *P1)]
+    t = time.perf_counter()
+    LO.block_bwd_skip_loops(*args, 1e-6)
+    dtl = time.perf_counter() - t
+    legs["pure_loops_C1_shape"] = {"value": round(tok / dtl, 2), "unit": "tokens/s", "cores": 1,
+                                   "sample": f"one pass over {tok} tokens of the C1 layer (d={c1.d_model}, f={c1.d_ff}, "
+                                             f"r={c1.rank}; the token-independent expand products dominate), pure Python loops, {dtl:.1f} s"}
     out["legs"] = legs
     return out
 

@@ -15,7 +15,8 @@ smoke check and the benchmark's cpu_baseline leg may call it.
 
 Every function below is pinned by tests that do not re-type its formula: finite
 differences, torch.autograd of an independently written module, the full-rank
-identity, projector algebra, and invariants (see tests/test_oracle_pins.py).
+identity, projector algebra, invariants, and a brute-force index-sum form in pure Python
+(oracle/mecefo_loops.py) on tiny inputs (see tests/test_oracle_pins.py).
 The paper prints no per-layer numeric example, so no printed value pins it.
 
 Row-major conventions (tokens along rows):

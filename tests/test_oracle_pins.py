@@ -412,6 +412,27 @@ def test_stack_forward_and_loss_gradient_match_a_torch_module_chain():
     assert relerr(dX_last, Xl.grad.numpy()) < 1e-10
 
 
+def test_brute_force_index_sums_agree_with_the_numpy_oracle():
+    """Brute force on tiny inputs: every output element of the neighbor-mode block backward written as an
+    explicit index sum in pure Python (oracle/mecefo_loops.py, no numpy, no matrix routine) against the
+    numpy oracle.  The two share no code; a transposed operand or a wrong index in either one fails here.
+    Non-square everywhere (b != d != f, three different ranks) so that no transposition goes unnoticed."""
+    from oracle import mecefo_loops as LO
+    rng = np.random.default_rng(11)
+    b, d, f = 5, 4, 7
+    rg, ru, rd = 2, 3, 5
+    H, dOut = rng.standard_normal((b, d)), rng.standard_normal((b, d))
+    gamma = 1 + 0.2 * rng.standard_normal(d)
+    Wg, Wu, Wd = rng.standard_normal((f, d)), rng.standard_normal((f, d)), rng.standard_normal((d, f))
+    Pg, Pu, Pd = rng.standard_normal((d, rg)), rng.standard_normal((d, ru)), rng.standard_normal((f, rd))
+    want = O.block_bwd_skip(H, dOut, gamma, Wg, Wu, Wd, Pg, Pu, Pd, EPS)
+    got = LO.block_bwd_skip_loops(H.tolist(), dOut.tolist(), gamma.tolist(), Wg.tolist(), Wu.tolist(), Wd.tolist(),
+                                  Pg.tolist(), Pu.tolist(), Pd.tolist(), EPS)
+    for k in ("dX", "dgamma", "dWg", "dWu", "dWd"):
+        assert np.asarray(got[k]).shape == want[k].shape, k
+        assert relerr(np.asarray(got[k]), want[k]) < 1e-12, k
+
+
 def test_saved_logsumexp_matches_library_routine_and_softmax():
     """The log-sum-exp that the forward keeps for the backward: checked against scipy's routine on
     the scaled, causally masked scores rebuilt from the cached Q and K, and exp(score - L) must
