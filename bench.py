@@ -647,6 +647,29 @@ def cpu_baseline(cfg):
         legs["fp32_one_thread"] = {"value": round(p1 * sample / dt1, 1), "unit": "tokens/s", "cores": 1,
                                    "sample": f"{p1} pass(es) over the first {sample} tokens (the token-independent "
                                              f"expand products of Eq. (2) included once per pass), float32 numpy, {dt1:.1f} s"}
+    # The smaller configs' layer shapes, float32 numpy: all cores (best of three passes) and one thread.
+    small = {}
+    for name in ("C1", "C2", "C3", "C4"):
+        c = I.CONFIGS[name]
+        rg = I.rng_for(c.index, 7)
+        w = I.ffn_weights(rg, c.d_model, c.d_ff, c.dtype)
+        h, do = I.gaussian_block_io(rg, c.tokens, c.d_model, c.dtype)
+        ps = [I._normal(rg, (n, c.rank), n ** -0.5) for n in (c.d_model, c.d_model, c.d_ff)]
+
+        def best(n=3):
+            ts = []
+            for _ in range(n):
+                t = time.perf_counter()
+                O.block_bwd_skip(h, do, w[3], w[0], w[1], w[2], *ps, 1e-6, dtype=np.float32)
+                ts.append(time.perf_counter() - t)
+            return min(ts)
+
+        e = {"tokens": c.tokens, "all_cores_tokens_per_s": round(c.tokens / best(), 1)}
+        if threadpool_limits is not None:
+            with threadpool_limits(limits=1):
+                e["one_thread_tokens_per_s"] = round(c.tokens / best(1 if name in ("C3", "C4") else 3), 1)
+        small[name] = e
+    legs["fp32_one_layer_small_configs"] = small
     # Pure-loop form (explicit index sums, no numpy) on the tiny config C1's layer shape, a few tokens.
     from oracle import mecefo_loops as LO
     c1 = I.CONFIGS["C1"]
