@@ -276,7 +276,10 @@ void mecefo_counters_reset(int64_t* t, int n_layers);
  * lowrank[l].Pg/Pu/Pd) with mecefo_projection_refresh of its weights, warm-started from their present
  * contents, and t[l] is incremented after the layer's backward has been enqueued; standard-mode layers
  * leave t[l] alone.  The refresh decision is taken on the host while enqueuing: a captured graph replays
- * the decisions of the capture.  Workspace: mecefo_stack_mixed_workspace_bytes. */
+ * the decisions of the capture.  Workspace: mecefo_stack_mixed_workspace_bytes.
+ * Errors: modes, policy and the pointer arrays are checked before anything is enqueued; the per-layer
+ * argument checks run as each layer is reached, so when layer l is rejected the layers above it have
+ * already been enqueued and their counters advanced (the returned message names the failing check). */
 mecefo_status_t mecefo_stack_mixed_workspace_bytes(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
     int r_gate, int r_up, int r_down, size_t* out_bytes);
 mecefo_status_t mecefo_stack_bwd_mixed(const mecefo_ffn_desc_t* desc, const mecefo_attn_desc_t* attn,
