@@ -294,6 +294,11 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
   };
 
+  // The two waves that share a SIMD (w and w + 4) run the same instruction stream; a raised issue
+  // priority for one of them keeps the pair slightly out of step, so that one tends to issue MFMAs
+  // while the other waits on LDS.  Measured (same box, alternating runs): recompute +0.8 %, expand
+  // +2 %, the other launches unchanged; higher priority values gave nothing.
+  if (NT == 512 && wave >= 4) __builtin_amdgcn_s_setprio(1);
   const int nst = kt_end - kt_begin;
   // The (up to eight) tiles of a tile column run at the same time on one XCD and share their B panel.
   // Each starts its K loop at a different stage (rotation by the tile row, wrapping around), so that
