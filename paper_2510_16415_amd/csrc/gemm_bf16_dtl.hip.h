@@ -1,7 +1,10 @@
 // bf16 MFMA GEMM for gfx950 with direct-to-LDS operand staging.
 //
-// Same tiling as gemm_bf16.hip.h (256 x 256 output tile, eight wavefronts of 64 x 128,
-// v_mfma_f32_32x32x16_bf16), but the operand tiles never pass through registers:
+// Same tiling as gemm_bf16.hip.h (256 x 256 output tile, eight wavefronts of 64 x 128), with two
+// differences.  The products run on v_mfma_f32_16x16x32_bf16: on Gaussian operands the matrix cores
+// are power-limited, and this shape moves half the accumulator bytes per multiply-add of the 32x32x16
+// one -- a bare MFMA loop on random operands sustains 2100 TFLOP/s at 2.1 GHz with it against 1860 at
+// 1.83 GHz.  And the operand tiles never pass through registers:
 // `buffer_load_dwordx4 ... lds` writes 1 KiB per wavefront instruction straight into LDS
 // (lane i lands at base + 16 i).  K is cut into stages of BK (32 or 64) held in a ring of NS
 // LDS buffers; a buffer is refilled as soon as the barrier that ends its last use has passed,
@@ -13,7 +16,7 @@
 //     token contraction) stay in their memory order [64 k][256 rows] in LDS and are transposed
 //     on the way to the MFMA registers by ds_read_b64_tr_b16 (each 16-lane group turns four
 //     k-rows of 16 elements into four K-consecutive values per lane); their 16-byte chunks are
-//     XOR-swizzled by k so that the four k-rows of a group fall into different banks.
+//     XOR-swizzled by k so that the eight k-rows of a 32-lane pass fall into different banks.
 // Rows and K positions outside the matrices are fetched from outside the buffer (zeros).
 // A ragged K inside a 16-byte chunk cannot be masked on this path: the host only selects it
 // when K is a multiple of 8 or the bytes behind K are known to be zero.
@@ -67,8 +70,14 @@ __device__ inline void wait_fills_leave(int stages_left) {
 
 // ---- direct-to-LDS fill of one operand tile (256 rows x BK) --------------------------------
 // Swizzle of the K-contiguous layout [rows][BK]: physical 16-byte chunk = logical ^ kc_swz(row).
+// A 16-byte read of the 16x16x32 operand (lane l: row l % 16, chunk l / 16 of the step) is served 16
+// lanes per clock, and the lanes of a clock are eight rows at one chunk plus the other eight rows of
+// the block at the neighbouring chunk (lanes 0-7 with 24-31, 8-15 with 16-23, and the same in the
+// upper half-wave; found by measurement: SQ_LDS_BANK_CONFLICT).  Rows of equal parity share their half
+// of the 64 banks; XORing row bits 1-2 into chunk bits 1-2 spreads the four rows of a parity over the
+// even (or odd) chunks and leaves the other chunks to the neighbouring-chunk rows.
 template <int BK> __device__ inline int kc_swz(int row) {
-  if constexpr (BK == 64) return swz(row);                 // 8 chunks per 128-byte row
+  if constexpr (BK == 64) return row & 6;                  // 8 chunks per 128-byte row
   else return ((row >> 1) ^ (row >> 3)) & 3;               // 4 chunks per 64-byte row
 }
 
@@ -101,12 +110,14 @@ struct DmaKC {   // K-contiguous source; one wave instruction covers RPI consecu
   }
 };
 
-__device__ inline int ks_swz(int k) { return (k & 7) << 1; }   // XOR on the 16-byte chunk index
+__device__ inline int ks_swz(int k) { return ((k & 7) << 1) ^ (k & 8); }   // XOR on the 16-byte chunk index
 // Physical 16-byte chunk of logical chunk c (0..31, eight columns each) in k row k, and back.  A
-// transposing read takes, per pass of 32 lanes, 64 bytes (four chunks) of each of four consecutive k
-// rows; LDS serves 256 bytes per clock from 64 banks, so the 16 chunks of a pass must differ in their
-// low four bits.  The k row fills bits 1-2 (XOR with k), the second chunk pair of a row (bit 1 of c)
-// moves to the other half of the banks (bit 3).  The map is its own inverse.
+// transposing read takes, per pass of 32 lanes, 32 bytes (two chunks) of each of eight k rows: four
+// consecutive ones and the four that lie eight further on (the two 16-lane groups of a pass hold
+// neighbouring K groups of the 16x16x32 operand).  LDS serves 256 bytes per clock from 64 banks, so
+// the 16 chunks of a pass must differ in their low four bits: bit 0 is the chunk of the pair, the k
+// row fills bits 1-2 (XOR with its low bits) and bit 3 (XOR with k bits 2 and 3); the second chunk
+// pair of a row (bit 1 of c) also goes to the other half of the banks.  The map is its own inverse.
 __device__ inline int ks_fold(int c) { return c ^ ((c & 2) << 2); }
 __device__ inline int ks_phys(int c, int k) { return (ks_fold(c) ^ ks_swz(k)) & 31; }
 __device__ inline int ks_logical(int pos, int k) { return ks_fold((pos ^ ks_swz(k)) & 31); }
@@ -145,7 +156,8 @@ template <int BK, int NT, bool DUAL> struct DmaSel<BK, NT, false, DUAL> {
 };
 
 // ---- MFMA operand fetch from LDS ------------------------------------------------------
-// NB blocks of 32 rows.  K-contiguous tiles: one ds_read_b128 per block and K sub-step.
+// Operands of v_mfma_f32_16x16x32_bf16: NB blocks of 16 rows; lane l holds row l % 16 and the eight
+// K values 8 (l / 16) .. + 7 of a 32-K step.  K-contiguous tiles: one ds_read_b128 per block and step.
 template <int BK, int NB>
 struct FragKC {
   int base[NB];
@@ -153,42 +165,40 @@ struct FragKC {
   __device__ inline void init(int lane, const int (&rows)[NB]) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      const int row = rows[i] + (lane & 31);
-      base[i] = row * (BK * 2) + (((lane >> 5) ^ kc_swz<BK>(row)) << 4);
+      const int row = rows[i] + (lane & 15);
+      base[i] = row * (BK * 2) + (((lane >> 4) ^ kc_swz<BK>(row)) << 4);
     }
   }
-  __device__ inline void fetch(bf16x8_t (&f)[NB], const uint8_t* tile, int ks) const {
-#pragma unroll
-    for (int i = 0; i < NB; ++i) f[i] = *(const bf16x8_t*)(tile + (base[i] ^ (ks << 5)));
+  __device__ inline bf16x8_t fetch_one(int i, const uint8_t* tile, int step) const {
+    return *(const bf16x8_t*)(tile + (base[i] ^ (step << 6)));
   }
 };
 
-// K-strided tiles ([BK k][256 rows], 512 bytes per k): two transposing 8-byte reads per block.
+// K-strided tiles ([BK k][256 rows], 512 bytes per k): two transposing 8-byte reads per block.  Within
+// a 16-lane group source lane 4 kq + q4 supplies rows 4 q4 .. + 3 at k row kq; the read hands result
+// lane i the four K-consecutive values of row i.
 template <int BK, int NB>
 struct FragKS {
   int base[NB][2];
   __device__ inline void init(int lane, const int (&rows)[NB]) {
-    const int kq = (lane & 15) >> 2, hi = lane >> 5, b = (lane >> 4) & 1, q4 = lane & 3;
+    const int kq = (lane & 15) >> 2, g = lane >> 4, q4 = lane & 3;
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      const int m = rows[i] + 16 * b + 4 * q4;
+      const int m = rows[i] + 4 * q4;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const int k = 8 * hi + 4 * h + kq;
+        const int k = 8 * g + 4 * h + kq;
         base[i][h] = k * 512 + (ks_phys(m >> 3, k) << 4) + ((m & 7) << 1);
       }
     }
   }
-  __device__ inline void fetch(bf16x8_t (&f)[NB], const uint8_t* tile, int ks) const {
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
-      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + base[i][0] + ks * 16 * 512));
-      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + base[i][1] + ks * 16 * 512));
-      typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-      const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      f[i] = __builtin_bit_cast(bf16x8_t, v);
-    }
+  __device__ inline bf16x8_t fetch_one(int i, const uint8_t* tile, int step) const {
+    typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + base[i][0] + step * 32 * 512));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(tile + base[i][1] + step * 32 * 512));
+    typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+    const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, v);
   }
 };
 
@@ -209,8 +219,9 @@ template <int BK_, int NS_> struct DtlPipe {
 template <class Cfg, class Pipe, bool AKC, bool BKC, int EPI>
 __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args) {
   constexpr bool DUAL = epi_is_dual(EPI);
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::NT;
-  constexpr int BK = Pipe::BK, NS = Pipe::NS, KS = BK / 16, FPS = BK / 8;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT;
+  constexpr int TM = Cfg::WM / 16, TN = Cfg::WN / 16;     // 16x16 MFMA blocks per wave
+  constexpr int BK = Pipe::BK, NS = Pipe::NS, KS = BK / 32, FPS = BK / 8;
   constexpr int A_BYTES = Pipe::A_BYTES, STAGE = Pipe::STAGE_BYTES;
   static_assert(BM == 256 && BN == 256 && NT == 512, "direct-to-LDS path is built for 256x256 tiles, 8 waves");
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;
@@ -253,24 +264,24 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
 
   int a_rows[TM], b_rows[TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) a_rows[i] = wm * Cfg::WM + i * 32;
+  for (int i = 0; i < TM; ++i) a_rows[i] = wm * Cfg::WM + i * 16;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    if constexpr (DUAL) b_rows[j] = (j >= TN / 2 ? BN / 2 : 0) + wn * (Cfg::WN / 2) + (j % (TN / 2)) * 32;
-    else b_rows[j] = wn * Cfg::WN + j * 32;
+    if constexpr (DUAL) b_rows[j] = (j >= TN / 2 ? BN / 2 : 0) + wn * (Cfg::WN / 2) + (j % (TN / 2)) * 16;
+    else b_rows[j] = wn * Cfg::WN + j * 16;
   }
   typename FragSel<BK, TM, AKC>::type fa;
   typename FragSel<BK, TN, BKC>::type fb;
   fa.init(lane, a_rows);
   fb.init(lane, b_rows);
 
-  f32x16_t acc[TM][TN];
+  f32x4_t acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
   auto issue = [&](int kt, uint32_t stage) {
     const int seg = (kt >= kt_per_seg ? 1 : 0) + (kt >= 2 * kt_per_seg ? 1 : 0);
@@ -285,19 +296,30 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
     }
   };
 
-  bf16x8_t af[2][TM], bfr[2][TN];
-  auto mma = [&](int slot) {
+  // Fragments: A double-buffered by K step, B single-buffered -- a B block is reloaded for the next
+  // step right behind the MFMAs of its column, the last use of its present contents.
+  bf16x8_t af[2][TM], bfr[TN];
+  static_assert(TM <= TN, "the A reloads ride on the first columns of the step");
+  // One 32-K step: MFMAs column by column; behind column j the loads of the next step's B block j and
+  // (for j < TM) A block j from `next`, step `ns`.  (Behind the very last step of the K loop these
+  // loads fetch fragments nobody uses: cheaper than a branch per column.)
+  auto step = [&](int cur, const uint8_t* next, int ns) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+      for (int i = 0; i < TM; ++i)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[cur][i], bfr[j], acc[i][j], 0, 0, 0);
+      bfr[j] = fb.fetch_one(j, next + A_BYTES, ns);
+      if (j < TM) af[cur ^ 1][j] = fa.fetch_one(j, next, ns);
+    }
+    // The scheduler's built-in pattern that alternates single MFMAs with single LDS reads.  Measured
+    // against its other pattern, none, and an order pinned column by column (same box, alternating
+    // runs): the large launches +4 to +9 %.
+    __builtin_amdgcn_iglp_opt(1);
   };
-
   // The two waves that share a SIMD (w and w + 4) run the same instruction stream; a raised issue
   // priority for one of them keeps the pair slightly out of step, so that one tends to issue MFMAs
-  // while the other waits on LDS.  Measured (same box, alternating runs): recompute +0.8 %, expand
-  // +2 %, the other launches unchanged; higher priority values gave nothing.
+  // while the other waits on LDS.
   if (NT == 512 && wave >= 4) __builtin_amdgcn_s_setprio(1);
   const int nst = kt_end - kt_begin;
   // The (up to eight) tiles of a tile column run at the same time on one XCD and share their B panel.
@@ -319,67 +341,56 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_bf16_dtl_kernel(const KArgs args
       if (s < nst) issue(kmap(s), smem_addr + s * STAGE);
     wait_fills_leave<FPS>(min(NS, nst) - 1);
     __syncthreads();
-    fa.fetch(af[0], smem, 0);
-    fb.fetch(bfr[0], smem + A_BYTES, 0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = fa.fetch_one(i, smem, 0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[j] = fb.fetch_one(j, smem + A_BYTES, 0);
     int buf = 0;
+    static_assert(KS == 2, "two 32-K steps per stage");
     for (int kt = kt_begin; kt < kt_end; ++kt) {
       const uint8_t* sc = smem + buf * STAGE;
       const int nbuf = buf + 1 == NS ? 0 : buf + 1;
-#pragma unroll
-      for (int ks = 0; ks + 1 < KS; ++ks) {
-        fa.fetch(af[(ks + 1) & 1], sc, ks + 1);
-        fb.fetch(bfr[(ks + 1) & 1], sc + A_BYTES, ks + 1);
-        mma(ks & 1);
-        // Ask the scheduler to interleave the fragment reads of the next sub-step with the MFMAs of
-        // this one instead of issuing them as two blocks (its built-in GEMM patterns; 1 suits the dual
-        // product, whose sub-step has eight independent MFMAs on two B halves).  Measured, same box,
-        // alternating runs: dgrad_down +3.4 %, project +4.6 %, expand +6.4 %, recompute +1.2 %,
-        // dgrad_gate_up +0.9 %, contract +0.4 %.  The same hint on the last sub-step of a stage (which
-        // also carries the refill) changed nothing.
-        __builtin_amdgcn_iglp_opt(DUAL ? 1 : 0);
-      }
-      // Every fragment of this stage is in registers.  Wait for the next stage only (younger
-      // fills stay in flight), meet the other waves, then refill this buffer NS stages ahead.
+      step(0, sc, 1);
+      // Every fragment of this stage is in registers or on its way.  Wait for the next stage only
+      // (younger fills stay in flight), meet the other waves, then refill this buffer NS stages ahead.
       wait_fills_leave<FPS>(min(NS - 2, kt_end - kt - 2));
       __syncthreads();
       if (kt + NS < kt_end) issue(kmap(kt - kt_begin + NS), smem_addr + buf * STAGE);
-      if (kt + 1 < kt_end) {
-        fa.fetch(af[0], smem + nbuf * STAGE, 0);
-        fb.fetch(bfr[0], smem + nbuf * STAGE + A_BYTES, 0);
-      }
-      mma((KS - 1) & 1);
+      step(1, smem + nbuf * STAGE, 0);
       buf = nbuf;
     }
   }
 
   // Epilogue, staged through LDS so that global accesses are 16 bytes per lane and cover whole
-  // rows (bf16: eight columns per access, fp32: two accesses of four).  Accumulator element e of a 32x32 block sits at row
-  // 8*(e/4) + 4*(lane/32) + e%4, column lane%32; each wave writes 32 rows of its sub-tile as fp32
-  // into its own LDS slice (row stride RS floats, chosen so that the two half-waves hit
+  // rows (bf16: eight columns per access, fp32: two accesses of four).  Accumulator element e of a 16x16 block sits at row
+  // 4*(lane/16) + e, column lane%16; each wave writes 32 rows of its sub-tile as fp32
+  // into its own LDS slice (row stride RS floats, chosen so that the 16-lane groups hit
   // different banks), then reads rows back eight columns per lane.  The operand stages are
   // free at this point: the loop's last barrier followed every fragment fetch and every fill.
   {
     constexpr int TNO = DUAL ? TN / 2 : TN;
-    constexpr int W = TNO * 32;                 // columns per matrix in this wave's sub-tile
-    constexpr int RS = W + 8;                   // 4*RS % 64 == 32
+    constexpr int W = TNO * 16;                 // columns per matrix in this wave's sub-tile
+    constexpr int RS = W + 4;                   // 4*RS % 64 == 16: the four row groups of a store, and neighbouring rows of a read, fall on different banks
     constexpr int MAT = 32 * RS;                // floats per staged matrix
     float* ep = (float*)(smem + wave * Pipe::EP_WAVE_BYTES);
-    const int wr_off = (4 * (lane >> 5)) * RS + (lane & 31);
+    const int wr_off = (4 * (lane >> 4)) * RS + (lane & 15);
     constexpr int LPR = W / 8;                  // lanes per row when reading back
     constexpr int RPI = 64 / LPR;               // rows per read instruction
     const int rd_row = lane / LPR, rd_c8 = (lane % LPR) * 8;
     const int row_w = m0 + wm * Cfg::WM;
     const int col_w = n0 + wn * (DUAL ? Cfg::WN / 2 : Cfg::WN) + rd_c8;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM / 2; ++i) {        // 32 rows = two block rows at a time
 #pragma unroll
-      for (int j = 0; j < TNO; ++j)
+      for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int o = wr_off + (8 * (e >> 2) + (e & 3)) * RS + j * 32;
-          ep[o] = acc[i][j][e];
-          if constexpr (DUAL) ep[MAT + o] = acc[i][j + TN / 2][e];
-        }
+        for (int j = 0; j < TNO; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int o = wr_off + (16 * ih + e) * RS + j * 16;
+            ep[o] = acc[2 * i + ih][j][e];
+            if constexpr (DUAL) ep[MAT + o] = acc[2 * i + ih][j + TN / 2][e];
+          }
       // fp32 outputs: four columns per lane, so that one store instruction covers whole 512-byte row
       // pieces (with eight columns per lane each of the two 16-byte stores would fill every other
       // 16 bytes of its lines)
